@@ -1,0 +1,92 @@
+"""Host-side checks of the seeded input generators (CPU only)."""
+import numpy as np
+import pytest
+
+import workloads as W
+
+
+def test_config1_matches_its_statement():
+    st = W.make_verify_step(1)
+    assert st.batch == 4 and list(st.ctx_lens) == [128, 256, 384, 512] and list(st.spec_lens) == [1, 2, 3, 4]
+    assert st.total_q == 14 and st.total_draft == 10
+    assert st.q.shape == (14, 8, 64) and st.q.dtype == np.float32
+    assert st.k_pages.shape == (st.num_pages, 8, 16, 64)
+    assert st.target_logits.shape == (14, 1024) and st.draft_probs.shape == (10, 1024)
+    assert st.uniforms.shape == (14, 2) and st.uniforms.min() >= 0 and st.uniforms.max() < 1
+    assert np.allclose(st.draft_probs.sum(axis=1), 1.0, atol=1e-5)
+    assert 1.8 < st.target_logits.std() < 2.2
+
+
+def test_determinism_and_seed_dependence():
+    a, b = W.make_verify_step(1), W.make_verify_step(1)
+    c = W.make_verify_step(1, seed=77)
+    for f in ("q", "k_pages", "block_table", "target_logits", "draft_probs", "draft_tokens", "uniforms"):
+        assert np.array_equal(getattr(a, f), getattr(b, f), equal_nan=True)
+    assert not np.array_equal(a.q, c.q)
+
+
+def test_block_table_is_a_shuffled_partition_with_poison():
+    st = W.make_verify_step(2, batch=6, acceptance=False)
+    P = st.page_size
+    used = st.block_table[st.block_table >= 0]
+    assert len(np.unique(used)) == len(used) and used.max() < st.num_pages
+    assert st.num_pages >= int(np.ceil(1.25 * len(used))) - 1
+    assert not np.all(np.diff(used) == 1)                      # shuffled, not the identity layout
+    kv = st.k_pages.view(np.float16)
+    for i in range(st.batch):
+        n_pages = -(-int(st.ctx_lens[i]) // P)
+        assert np.all(st.block_table[i, :n_pages] >= 0) and np.all(st.block_table[i, n_pages:] == -1)
+        tail = int(st.ctx_lens[i]) % P
+        last = st.block_table[i, n_pages - 1]
+        assert not np.isnan(kv[last, :, :tail or P]).any()
+        if tail:
+            assert np.isnan(kv[last, :, tail:]).all()
+    unused = np.setdiff1d(np.arange(st.num_pages), used)
+    assert np.isnan(kv[unused]).all()
+
+
+@pytest.mark.parametrize("cfg,lo,hi,kmax", [(2, 256, 2048, 8), (3, 128, 4096, 6), (4, 2048, 8192, 5),
+                                            (5, 1024, 2048, 1)])
+def test_ragged_structure_ranges(cfg, lo, hi, kmax):
+    st = W.make_verify_step(cfg, attention=False, acceptance=False)
+    assert st.batch == {2: 32, 3: 128, 4: 64, 5: 256}[cfg]
+    assert st.ctx_lens.min() >= lo and st.ctx_lens.max() <= hi
+    assert st.spec_lens.min() >= 0 and st.spec_lens.max() <= kmax
+    assert np.all(st.ctx_lens >= st.spec_lens + 1)
+    if cfg == 3:      # mean draft length in the range the paper's Table 2 reports for its policy
+        assert 2.5 < st.spec_lens.mean() < 3.7
+    if cfg == 5:
+        assert set(np.unique(st.temperature)) <= {np.float32(0), np.float32(0.7), np.float32(1.0)}
+
+
+def test_draft_tokens_have_positive_draft_probability_and_greedy_drafter():
+    st = W.make_custom_step(3, ctx_lens=[32] * 6, spec_lens=[3, 2, 0, 4, 1, 2], vocab=2000,
+                            logits_dtype="bf16", temperature=[1, 0, 1, 0.7, 0, 1], attention=False,
+                            logits_sigma=3.0, noise_sigma=1.5, draft_temp=1.2)
+    qd = W.to_f64(st.draft_probs, "bf16")
+    assert np.all(qd[np.arange(st.total_draft), st.draft_tokens] > 0)
+    cu = st.cu_q
+    for i in (1, 4):
+        for j in range(int(st.spec_lens[i])):
+            d = cu[i] - i + j
+            assert st.draft_tokens[d] == np.argmax(qd[d])
+
+
+def test_bf16_storage_roundtrip():
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 1e-3, 3.0e38, np.inf], dtype=np.float32)
+    b = W.f32_to_bf16_bits(x)
+    back = W.bf16_bits_to_f32(b)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.0 + 2.0 ** -6)
+    assert back[3] == -2.5 and abs(back[4] - 1e-3) < 1e-5 and np.isinf(back[6])
+    assert np.isnan(W.bf16_bits_to_f32(W.f32_to_bf16_bits(np.array([np.nan], np.float32))))[0]
+
+
+def test_algorithmic_bytes_formula():
+    st = W.make_custom_step(5, ctx_lens=[40, 17], spec_lens=[2, 0], n_q_heads=4, n_kv_heads=2, head_dim=32,
+                            dtype="bf16", vocab=64, logits_dtype="bf16", temperature=[1.0, 0.0])
+    b = W.algorithmic_bytes(st)
+    assert b["kv"] == (40 + 17) * 2 * 2 * 32 * 2
+    assert b["q_out"] == 4 * 4 * 32 * 2 * 2
+    assert b["block_table"] == (3 + 2) * 4
+    assert b["logits"] == 4 * 64 * 2 and b["probs"] == 2 * 64 * 2
+    assert b["total"] == b["attn"] + b["accept"]
