@@ -1,0 +1,194 @@
+/*
+ * adaspec.h - C ABI of the MI355X (gfx950) ragged verification step.
+ *
+ * One speculative-decoding verification step over a batch whose requests carry
+ * different numbers of draft tokens (the per-request speculative lengths that
+ * the paper's Confidence Prior Verifier leaves after draft-token elimination:
+ * Alg. 2, Sec. 5.2).  Request i has k_i = spec_lens[i] draft tokens and
+ * n_i = k_i + 1 query rows: row 0 is the last committed token, rows 1..k_i are
+ * the drafts.  TQ = sum n_i, TD = sum k_i.  Rows of request i start at
+ * cu_q[i] = sum_{j<i} n_j; its draft rows start at cu_q[i] - i.
+ *
+ * Conventions for every call
+ *   - Every pointer except the dims struct is a DEVICE pointer owned by the
+ *     caller.  The library allocates nothing, frees nothing and never
+ *     synchronises; work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream).
+ *   - `workspace` is caller-provided device scratch of at least
+ *     *_workspace_bytes(dims) bytes, 256-byte aligned; its contents are
+ *     undefined before and after a call.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Return value: 0 (ADASPEC_OK) or a negative adaspec_status.  On error
+ *     nothing has been enqueued.  Errors the host can see (null pointers, bad
+ *     dims, unsupported dtype, misalignment, small workspace) are reported;
+ *     inconsistent DEVICE data (ctx_lens[i] < n_i, page id out of range,
+ *     sum(spec_lens)+batch != total_q) is undefined behaviour unless checked
+ *     first with adaspec_check_ragged_inputs().
+ *   - Outputs are fully overwritten.  Results are deterministic: the same
+ *     inputs give bit-identical outputs (no floating-point atomics).
+ */
+#ifndef ADASPEC_H
+#define ADASPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADASPEC_OK = 0,
+    ADASPEC_ERR_NULL = -1,        /* a required pointer is NULL                    */
+    ADASPEC_ERR_DIM = -2,         /* a size is negative/zero/inconsistent          */
+    ADASPEC_ERR_DTYPE = -3,       /* unknown or unsupported element type           */
+    ADASPEC_ERR_ALIGN = -4,       /* pointer or row stride not 16-byte aligned     */
+    ADASPEC_ERR_WORKSPACE = -5,   /* workspace smaller than *_workspace_bytes()    */
+    ADASPEC_ERR_UNSUPPORTED = -6, /* shape outside what the kernels implement      */
+    ADASPEC_ERR_HIP = -7          /* a HIP launch failed                           */
+} adaspec_status;
+
+typedef enum { ADASPEC_F32 = 0, ADASPEC_F16 = 1, ADASPEC_BF16 = 2 } adaspec_dtype;
+
+/* Kernel selection for adaspec_verify_attn / adaspec_accept.  AUTO picks the
+ * matrix-core (attention) / register-resident (accept) kernel when the shape
+ * allows and the portable vector kernel otherwise; the other two values force
+ * one of them (ADASPEC_ERR_UNSUPPORTED if the shape does not fit it). */
+typedef enum { ADASPEC_PATH_AUTO = 0, ADASPEC_PATH_VECTOR = 1, ADASPEC_PATH_FAST = 2 } adaspec_path;
+
+/* ------------------------------------------------------------------------
+ * Verification attention (paper Sec. 2.2: the target scores all SL+1 positions
+ * in one pass, position t conditioned on the committed tokens and the drafts
+ * before it; Eq. 4: the context count grows by one per position; Sec. 6: the
+ * KV cache is paged).
+ *
+ * Row j of request i sits at position pos = ctx_lens[i] - n_i + j and attends
+ * to cached tokens 0..pos of its request:
+ *     out = softmax(scale * q . K[0..pos]) V[0..pos]
+ * q head h reads kv head h / (n_q_heads / n_kv_heads).
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t batch;              /* B >= 0                                              */
+    int32_t total_q;            /* TQ = sum(spec_lens[i] + 1); known to the host policy */
+    int32_t max_spec_len;       /* upper bound on spec_lens[i]                          */
+    int32_t n_q_heads;          /* Hq                                                   */
+    int32_t n_kv_heads;         /* Hkv, divides Hq                                      */
+    int32_t head_dim;           /* d: 64 or 128 (vector path: any multiple of 8 <= 256) */
+    int32_t page_size;          /* P = 16 tokens                                        */
+    int32_t num_pages;          /* pages in k_pages / v_pages                           */
+    int32_t max_pages_per_req;  /* row stride of block_table                            */
+    int32_t dtype;              /* adaspec_dtype of q, k_pages, v_pages                 */
+    int32_t out_dtype;          /* adaspec_dtype of out: same as dtype, or ADASPEC_F32
+                                   (the fp32 accumulator before the final rounding)     */
+    int32_t path;               /* adaspec_path                                         */
+    float   scale;              /* softmax scale; 0 means 1/sqrt(head_dim)              */
+} adaspec_attn_dims;
+
+/* Device scratch needed by adaspec_verify_attn for these dims (0 on bad dims). */
+size_t adaspec_verify_attn_workspace_bytes(const adaspec_attn_dims *dims);
+
+/*
+ * q           [TQ][Hq][d]                       request-major rows (see cu_q above)
+ * k_pages     [num_pages][Hkv][P][d]            one (page, kv head) block is contiguous
+ * v_pages     same layout as k_pages
+ * block_table [B][max_pages_per_req] int32      page id of tokens 16p..16p+15 of request i;
+ *                                               entries past ceil(ctx_lens[i]/P) are ignored
+ * ctx_lens    [B] int32   L_i: cached tokens of request i INCLUDING its n_i query tokens
+ *                         (their K/V are already in the pages); L_i >= n_i
+ * spec_lens   [B] int32   k_i in [0, max_spec_len]
+ * out         [TQ][Hq][d] of out_dtype; one round-to-nearest-even from the fp32 accumulator
+ * Slots of a request's last page beyond L_i, and pages no request uses, are never
+ * allowed to influence the result (they may hold NaN).
+ * q, k_pages, v_pages, out must be 16-byte aligned.
+ */
+int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
+                        const int32_t *block_table, const int32_t *ctx_lens,
+                        const int32_t *spec_lens, void *out,
+                        const adaspec_attn_dims *dims,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Acceptance (paper Sec. 2.2 and Fig. 1 for the greedy form: accept a draft
+ * while it equals the target's choice, stop at the first mismatch, emit the
+ * target's token there; Sec. 4.2: one bonus token is always produced.  The
+ * stochastic form is the speculative-sampling rule of the works the paper
+ * cites for speculative decoding in Sec. 1.)
+ *
+ * Per request, left to right over its drafts x_0..x_{k-1}, temperature T:
+ *   T > 0: p = softmax(logits_row / T), q = the draft row.
+ *          accept x_j iff uniforms[row][0] < p[x_j] / q[x_j]  (q[x_j] == 0 accepts);
+ *          on the first rejection emit the smallest t whose inclusive prefix sum
+ *          of r = max(0, p - q) exceeds uniforms[row][1] * sum(r), and stop;
+ *          (if sum(r) == 0 the token is drawn from p the same way);
+ *          if every draft is accepted emit a token drawn from the bonus row's p
+ *          with that row's uniforms[.][1].
+ *   T == 0: accept x_j iff x_j == argmax(logits_row) (lowest index on ties);
+ *          the emitted token at the stop / bonus row is that argmax.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t batch;              /* B                                                   */
+    int32_t total_q;            /* TQ: rows of target_logits                           */
+    int32_t total_draft;        /* TD = TQ - B: rows of draft_probs                    */
+    int32_t max_spec_len;       /* upper bound on spec_lens[i]                         */
+    int32_t vocab;              /* V                                                   */
+    int32_t logits_dtype;       /* adaspec_dtype of target_logits                      */
+    int32_t probs_dtype;        /* adaspec_dtype of draft_probs                        */
+    int32_t out_stride;         /* row stride of out_tokens, >= max_spec_len + 1       */
+    int64_t logits_row_stride;  /* elements between logits rows, >= V                  */
+    int64_t probs_row_stride;   /* elements between draft_probs rows, >= V             */
+    int32_t path;               /* adaspec_path                                        */
+    int32_t reserved;
+} adaspec_accept_dims;
+
+size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims);
+
+/*
+ * target_logits [TQ][V]   request i owns rows cu_q[i]..cu_q[i]+k_i; row j judges draft j,
+ *                         row k_i is the bonus row
+ * draft_probs   [TD][V]   request i owns rows cu_q[i]-i ..; the distribution x_j was drawn from
+ *                         (final probabilities: the temperature is NOT applied to them)
+ * draft_tokens  [TD] int32 in [0, V)
+ * uniforms      [TQ][2] float32 in [0, 1): [r][0] accept test, [r][1] inverse-CDF draw
+ * spec_lens     [B] int32
+ * temperature   [B] float32 >= 0, per request
+ * out_tokens    [B][out_stride] int32: a_i accepted drafts, one recovered/bonus token, then -1
+ * out_accept_len[B] int32: a_i in [0, k_i]; request i emitted a_i + 1 tokens
+ * Rows after a request's first rejection are still evaluated (the rows are independent;
+ * the sequential rule is applied to the per-row results afterwards).
+ * The register-resident path needs 16-bit logits/probs, V % 8 == 0, V <= 131072, strides % 8 == 0
+ * and 16-byte aligned base pointers; anything else runs on the vector path.
+ */
+int adaspec_accept(const void *target_logits, const void *draft_probs,
+                   const int32_t *draft_tokens, const float *uniforms,
+                   const int32_t *spec_lens, const float *temperature,
+                   int32_t *out_tokens, int32_t *out_accept_len,
+                   const adaspec_accept_dims *dims,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Optional device-side check of the ragged metadata (for callers that cannot
+ * vouch for it): enqueues one small kernel that writes a bit mask to
+ * *err_flags (device int32): bit 0 spec_lens[i] outside [0, max_spec_len],
+ * bit 1 ctx_lens[i] < n_i or more pages than max_pages_per_req, bit 2 a used
+ * block_table entry outside [0, num_pages), bit 3 sum(n_i) != total_q.
+ * 0 means consistent.
+ * ---------------------------------------------------------------------- */
+int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_lens,
+                                const int32_t *spec_lens, const adaspec_attn_dims *dims,
+                                int32_t *err_flags, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Per-kernel timing for benchmarks: when both events are non-NULL, the next
+ * calls record `start` (hipEvent_t) right before and `stop` right after the
+ * launch of the selected kernel on the call's stream.  Pass NULLs to clear.
+ * which: 0 = attention main kernel, 1 = accept main kernel.
+ * ---------------------------------------------------------------------- */
+int adaspec_set_timing_events(int which, void *start_event, void *stop_event);
+
+const char *adaspec_status_string(int status);
+int adaspec_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADASPEC_H */

@@ -1,0 +1,10 @@
+"""MI355X-native ragged verification step (attention + acceptance) behind a C ABI.
+
+``binding`` wraps ``libadaspec.so``; ``build`` compiles it.  Nothing here falls
+back to a CPU or PyTorch implementation.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    AdaspecError, AttnDims, AcceptDims, accept, verify_attn, check_ragged_inputs,
+    set_timing_events, status_string, version, lib,
+)

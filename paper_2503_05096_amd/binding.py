@@ -1,0 +1,215 @@
+"""Thin Python binding of libadaspec.so (see include/adaspec.h).
+
+Argument marshalling only: every step of the verification path runs inside the
+library's HIP kernels.  PyTorch supplies device memory and streams.  There is
+no CPU fallback: if the library has not been built, importing it fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadaspec.so")
+
+F32, F16, BF16 = 0, 1, 2
+PATH_AUTO, PATH_VECTOR, PATH_FAST = 0, 1, 2
+_PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST}
+
+EXPORTS = (
+    "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
+    "adaspec_accept_workspace_bytes", "adaspec_accept",
+    "adaspec_check_ragged_inputs", "adaspec_set_timing_events",
+    "adaspec_status_string", "adaspec_version",
+)
+
+
+class AttnDims(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("total_q", C.c_int32), ("max_spec_len", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_size", C.c_int32), ("num_pages", C.c_int32), ("max_pages_per_req", C.c_int32),
+                ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("path", C.c_int32),
+                ("scale", C.c_float)]
+
+
+class AcceptDims(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("total_q", C.c_int32), ("total_draft", C.c_int32),
+                ("max_spec_len", C.c_int32), ("vocab", C.c_int32), ("logits_dtype", C.c_int32),
+                ("probs_dtype", C.c_int32), ("out_stride", C.c_int32),
+                ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64),
+                ("path", C.c_int32), ("reserved", C.c_int32)]
+
+
+class AdaspecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; "
+                "g.build()' or python paper_2503_05096_amd/build.py). There is no fallback path.")
+        L = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        L.adaspec_verify_attn_workspace_bytes.restype = C.c_size_t
+        L.adaspec_verify_attn_workspace_bytes.argtypes = [C.POINTER(AttnDims)]
+        L.adaspec_verify_attn.restype = C.c_int
+        L.adaspec_verify_attn.argtypes = [vp] * 7 + [C.POINTER(AttnDims), vp, C.c_size_t, vp]
+        L.adaspec_accept_workspace_bytes.restype = C.c_size_t
+        L.adaspec_accept_workspace_bytes.argtypes = [C.POINTER(AcceptDims)]
+        L.adaspec_accept.restype = C.c_int
+        L.adaspec_accept.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
+        L.adaspec_check_ragged_inputs.restype = C.c_int
+        L.adaspec_check_ragged_inputs.argtypes = [vp, vp, vp, C.POINTER(AttnDims), vp, vp]
+        L.adaspec_set_timing_events.restype = C.c_int
+        L.adaspec_set_timing_events.argtypes = [C.c_int, vp, vp]
+        L.adaspec_status_string.restype = C.c_char_p
+        L.adaspec_status_string.argtypes = [C.c_int]
+        L.adaspec_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().adaspec_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().adaspec_version())
+
+
+# --------------------------------------------------------------------------
+# torch-facing wrappers
+# --------------------------------------------------------------------------
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}[t.dtype]
+
+
+def _torch_dtype(code: int):
+    import torch
+    return {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}[code]
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes: int, device, workspace):
+    import torch
+    if workspace is not None:
+        return workspace
+    key = (str(device),)
+    ws = _ws_cache.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        _ws_cache[key] = ws
+    return ws
+
+
+def attn_dims(q, k_pages, block_table, *, max_spec_len: int, scale: float = 0.0,
+              out_dtype: Optional[int] = None, path: str = "auto") -> AttnDims:
+    dt = _dtype_code(q)
+    TQ, Hq, d = q.shape
+    num_pages, Hkv, P, _ = k_pages.shape
+    B, max_pages = block_table.shape
+    return AttnDims(B, TQ, int(max_spec_len), Hq, Hkv, d, P, num_pages, max_pages, dt,
+                    dt if out_dtype is None else int(out_dtype), _PATHS[path], float(scale))
+
+
+def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None, *,
+                max_spec_len: int, scale: float = 0.0, out_dtype: Optional[int] = None,
+                path: str = "auto", workspace=None, stream=None):
+    """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d]."""
+    import torch
+    dims = attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
+                     out_dtype=out_dtype, path=path)
+    for t in (q, k_pages, v_pages, block_table, ctx_lens, spec_lens):
+        assert t.is_cuda and t.is_contiguous()
+    assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32 and spec_lens.dtype == torch.int32
+    assert v_pages.shape == k_pages.shape and v_pages.dtype == k_pages.dtype == q.dtype
+    if out is None:
+        out = torch.empty(q.shape, dtype=_torch_dtype(dims.out_dtype), device=q.device)
+    L = lib()
+    need = L.adaspec_verify_attn_workspace_bytes(C.byref(dims))
+    if need == 0 and dims.batch > 0:
+        raise AdaspecError(L.adaspec_verify_attn(None, None, None, None, None, None, None, C.byref(dims),
+                                                 None, 0, None) or -2, "adaspec_verify_attn (dims)")
+    ws = _workspace(need, q.device, workspace)
+    rc = L.adaspec_verify_attn(q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+                               block_table.data_ptr(), ctx_lens.data_ptr(), spec_lens.data_ptr(),
+                               out.data_ptr(), C.byref(dims), ws.data_ptr(), ws.numel(),
+                               _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_verify_attn")
+    return out
+
+
+def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, *,
+           max_spec_len: int, out_tokens=None, out_accept_len=None, out_stride: Optional[int] = None,
+           path: str = "auto", workspace=None, stream=None) -> Tuple[object, object]:
+    """adaspec_accept on device tensors; returns (out_tokens [B][out_stride], out_accept_len [B])."""
+    import torch
+    TQ, V = target_logits.shape
+    B = spec_lens.shape[0]
+    TD = TQ - B
+    out_stride = int(max_spec_len) + 1 if out_stride is None else int(out_stride)
+    for t in (target_logits, uniforms, spec_lens, temperature):
+        assert t.is_cuda
+    assert target_logits.stride(1) == 1 and uniforms.is_contiguous()
+    assert uniforms.dtype == torch.float32 and temperature.dtype == torch.float32
+    assert spec_lens.dtype == torch.int32
+    if TD > 0:
+        assert draft_probs.shape == (TD, V) and draft_probs.stride(1) == 1
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (TD,)
+        pdt, pstride = _dtype_code(draft_probs), draft_probs.stride(0)
+        pp, tp = draft_probs.data_ptr(), draft_tokens.data_ptr()
+    else:
+        pdt, pstride, pp, tp = _dtype_code(target_logits), V, None, None
+    dims = AcceptDims(B, TQ, TD, int(max_spec_len), V, _dtype_code(target_logits), pdt, out_stride,
+                      target_logits.stride(0), pstride, _PATHS[path], 0)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, out_stride), dtype=torch.int32, device=target_logits.device)
+    if out_accept_len is None:
+        out_accept_len = torch.empty((B,), dtype=torch.int32, device=target_logits.device)
+    L = lib()
+    need = L.adaspec_accept_workspace_bytes(C.byref(dims))
+    ws = _workspace(max(need, 256), target_logits.device, workspace)
+    rc = L.adaspec_accept(target_logits.data_ptr(), pp, tp, uniforms.data_ptr(), spec_lens.data_ptr(),
+                          temperature.data_ptr(), out_tokens.data_ptr(), out_accept_len.data_ptr(),
+                          C.byref(dims), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_accept")
+    return out_tokens, out_accept_len
+
+
+def check_ragged_inputs(block_table, ctx_lens, spec_lens, dims: AttnDims, stream=None) -> int:
+    """Runs the device-side metadata check and returns the flag word (synchronises)."""
+    import torch
+    flags = torch.zeros(1, dtype=torch.int32, device=block_table.device)
+    rc = lib().adaspec_check_ragged_inputs(block_table.data_ptr(), ctx_lens.data_ptr(),
+                                           spec_lens.data_ptr(), C.byref(dims), flags.data_ptr(),
+                                           _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_check_ragged_inputs")
+    return int(flags.item())
+
+
+def set_timing_events(which: int, start_event_ptr: Optional[int], stop_event_ptr: Optional[int]) -> None:
+    rc = lib().adaspec_set_timing_events(int(which), start_event_ptr, stop_event_ptr)
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_set_timing_events")

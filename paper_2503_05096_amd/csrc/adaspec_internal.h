@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of libadaspec.so:
+// workspace layouts and the launchers each kernel file exports.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/adaspec.h"
+
+namespace adaspec {
+
+// ---- attention workspace -------------------------------------------------
+// A "work item" is one (request, KV split); splits of a request have equal
+// length (a multiple of the kernel's token block).  Items are stored densely
+// in request order; the plan kernel builds the list on the device because the
+// context lengths live there.
+struct AttnPlan {
+    int   split_tokens;     // S: maximum tokens per split
+    int   block_tokens;     // split lengths are rounded up to a multiple of this
+    int   max_items;        // host-side bound on the number of work items
+    int   max_rows;         // (max_spec_len + 1) * G
+    // byte offsets into the workspace
+    size_t off_header;      // int32[16]: [0] n_items, [1] ticket counter
+    size_t off_cu_q;        // int32[B + 1]
+    size_t off_row_req;     // int32[TQ]
+    size_t off_split_base;  // int32[B + 1]: first item of each request
+    size_t off_item_req;    // int32[max_items]
+    size_t off_part_ml;     // float[max_items][Hkv][max_rows][2]  (m in log2 units, l)
+    size_t off_part_o;      // float[max_items][Hkv][max_rows][d]
+    size_t total_bytes;
+};
+
+// Length of every split of a request with L cached tokens cut into ns splits.
+__host__ __device__ inline int split_len_of(int L, int ns, int block_tokens)
+{
+    const int per = (L + ns - 1) / ns;
+    return (per + block_tokens - 1) / block_tokens * block_tokens;
+}
+
+AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path);
+bool attn_fast_path_supported(const adaspec_attn_dims &d);
+
+struct AttnArgs {
+    const void *q, *k_pages, *v_pages;
+    const int32_t *block_table, *ctx_lens, *spec_lens;
+    void *out;
+    adaspec_attn_dims dims;
+    float scale_log2;       // scale * log2(e)
+    AttnPlan plan;
+    char *ws;
+    hipStream_t stream;
+};
+
+hipError_t launch_attn_plan(const AttnArgs &a);
+hipError_t launch_attn_vector(const AttnArgs &a);
+hipError_t launch_attn_mfma(const AttnArgs &a);
+hipError_t launch_attn_combine(const AttnArgs &a);
+
+// ---- accept workspace ------------------------------------------------------
+struct AcceptPlan {
+    size_t off_cu_q;        // int32[B + 1]
+    size_t off_row_req;     // int32[TQ]
+    size_t off_row_flag;    // int32[TQ]  1 = accepted (or bonus row)
+    size_t off_row_cand;    // int32[TQ]  token to emit if the request stops at this row
+    size_t total_bytes;
+};
+AcceptPlan make_accept_plan(const adaspec_accept_dims &d);
+bool accept_fast_path_supported(const adaspec_accept_dims &d, const void *logits, const void *probs);
+
+struct AcceptArgs {
+    const void *logits, *probs;
+    const int32_t *draft_tokens;
+    const float *uniforms;
+    const int32_t *spec_lens;
+    const float *temperature;
+    int32_t *out_tokens, *out_accept_len;
+    adaspec_accept_dims dims;
+    AcceptPlan plan;
+    char *ws;
+    hipStream_t stream;
+};
+
+hipError_t launch_accept_plan(const AcceptArgs &a);
+hipError_t launch_accept_vector(const AcceptArgs &a);
+hipError_t launch_accept_fast(const AcceptArgs &a);
+hipError_t launch_accept_emit(const AcceptArgs &a);
+
+hipError_t launch_check_ragged(const int32_t *block_table, const int32_t *ctx_lens,
+                               const int32_t *spec_lens, const adaspec_attn_dims &d,
+                               int32_t *err_flags, hipStream_t stream);
+
+}  // namespace adaspec

@@ -1,0 +1,233 @@
+// C ABI entry points of libadaspec.so: host-side validation, workspace layout
+// and the launch sequence of each call.  No HIP call is made before the
+// arguments have been validated, so the error paths work on a machine with no
+// GPU.
+#include <math.h>
+#include <string.h>
+
+#include "adaspec_internal.h"
+#include "device_utils.h"
+
+namespace adaspec {
+
+static hipEvent_t g_ev_start[2] = {nullptr, nullptr};
+static hipEvent_t g_ev_stop[2] = {nullptr, nullptr};
+
+static bool dtype_ok(int dt) { return dt == ADASPEC_F32 || dt == ADASPEC_F16 || dt == ADASPEC_BF16; }
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int validate_attn_dims(const adaspec_attn_dims *d)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->batch < 0 || d->total_q < d->batch || d->max_spec_len < 0) return ADASPEC_ERR_DIM;
+    if ((int64_t)d->total_q > (int64_t)d->batch * (d->max_spec_len + 1)) return ADASPEC_ERR_DIM;
+    if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads) return ADASPEC_ERR_DIM;
+    if (d->num_pages <= 0 || d->max_pages_per_req <= 0) return ADASPEC_ERR_DIM;
+    if (d->head_dim <= 0) return ADASPEC_ERR_DIM;
+    if (!dtype_ok(d->dtype) || !dtype_ok(d->out_dtype)) return ADASPEC_ERR_DTYPE;
+    if (d->out_dtype != d->dtype && d->out_dtype != ADASPEC_F32) return ADASPEC_ERR_DTYPE;
+    if (d->page_size != 16) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->head_dim % 8 || d->head_dim > 256) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
+    if (!(d->scale >= 0.0f) || isinf(d->scale)) return ADASPEC_ERR_DIM;
+    if (d->path == ADASPEC_PATH_FAST && !attn_fast_path_supported(*d)) return ADASPEC_ERR_UNSUPPORTED;
+    return ADASPEC_OK;
+}
+
+static bool attn_use_fast(const adaspec_attn_dims &d)
+{
+    if (d.path == ADASPEC_PATH_VECTOR) return false;
+    return attn_fast_path_supported(d);
+}
+
+AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
+{
+    AttnPlan p;
+    const int G = d.n_q_heads / d.n_kv_heads;
+    // The matrix-core kernel runs 4 wavefronts per work item, each over up to 256
+    // tokens, and merges them on chip; the vector kernel runs one wavefront per
+    // item.  With few (request, kv head) pairs the splits are shortened so that
+    // the chip still sees enough independent items.
+    const int64_t pairs = (int64_t)d.batch * d.n_kv_heads;
+    if (fast_path) {
+        p.block_tokens = 32;
+        p.split_tokens = pairs >= 512 ? 1024 : (pairs >= 128 ? 512 : 256);
+    } else {
+        p.block_tokens = 64;
+        p.split_tokens = 256;
+    }
+    const int64_t max_ctx = (int64_t)d.max_pages_per_req * d.page_size;
+    const int64_t per_req = (max_ctx + p.split_tokens - 1) / p.split_tokens;
+    p.max_items = (int)((int64_t)d.batch * per_req);
+    p.max_rows = (d.max_spec_len + 1) * G;
+    size_t off = 0;
+    p.off_header = off;     off = align_up(off + 16 * sizeof(int32_t), 256);
+    p.off_cu_q = off;       off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
+    p.off_row_req = off;    off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 4, 256);
+    p.off_split_base = off; off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
+    p.off_item_req = off;   off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
+    p.off_part_ml = off;
+    off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * 2 * sizeof(float), 256);
+    p.off_part_o = off;
+    off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * d.head_dim * sizeof(float), 256);
+    p.total_bytes = off;
+    return p;
+}
+
+static int validate_accept_dims(const adaspec_accept_dims *d)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->batch < 0 || d->total_q < d->batch || d->max_spec_len < 0) return ADASPEC_ERR_DIM;
+    if (d->total_draft != d->total_q - d->batch) return ADASPEC_ERR_DIM;
+    if ((int64_t)d->total_q > (int64_t)d->batch * (d->max_spec_len + 1)) return ADASPEC_ERR_DIM;
+    if (d->vocab <= 0) return ADASPEC_ERR_DIM;
+    if (!dtype_ok(d->logits_dtype) || !dtype_ok(d->probs_dtype)) return ADASPEC_ERR_DTYPE;
+    if (d->logits_row_stride < d->vocab || d->probs_row_stride < d->vocab) return ADASPEC_ERR_DIM;
+    if (d->out_stride < d->max_spec_len + 1) return ADASPEC_ERR_DIM;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
+    return ADASPEC_OK;
+}
+
+AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
+{
+    AcceptPlan p;
+    size_t off = 0;
+    const size_t tq = (size_t)(d.total_q > 0 ? d.total_q : 1);
+    p.off_cu_q = off;     off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
+    p.off_row_req = off;  off = align_up(off + tq * 4, 256);
+    p.off_row_flag = off; off = align_up(off + tq * 4, 256);
+    p.off_row_cand = off; off = align_up(off + tq * 4, 256);
+    p.total_bytes = off;
+    return p;
+}
+
+}  // namespace adaspec
+
+using namespace adaspec;
+
+extern "C" {
+
+size_t adaspec_verify_attn_workspace_bytes(const adaspec_attn_dims *dims)
+{
+    if (validate_attn_dims(dims) != ADASPEC_OK) return 0;
+    return make_attn_plan(*dims, attn_use_fast(*dims)).total_bytes;
+}
+
+int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
+                        const int32_t *block_table, const int32_t *ctx_lens,
+                        const int32_t *spec_lens, void *out, const adaspec_attn_dims *dims,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_attn_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    if (dims->batch == 0) return ADASPEC_OK;
+    if (!q || !k_pages || !v_pages || !block_table || !ctx_lens || !spec_lens || !out || !workspace)
+        return ADASPEC_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return ADASPEC_ERR_ALIGN;
+    AttnArgs a;
+    const bool fast = attn_use_fast(*dims);
+    a.plan = make_attn_plan(*dims, fast);
+    if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;
+    a.q = q; a.k_pages = k_pages; a.v_pages = v_pages;
+    a.block_table = block_table; a.ctx_lens = ctx_lens; a.spec_lens = spec_lens;
+    a.out = out; a.dims = *dims; a.ws = static_cast<char *>(workspace);
+    a.stream = static_cast<hipStream_t>(stream);
+    const float scale = dims->scale > 0.0f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
+    a.scale_log2 = scale * 1.4426950408889634f;
+
+    if (launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_start[0], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    hipError_t e = fast ? launch_attn_mfma(a) : launch_attn_vector(a);
+    if (e != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_stop[0], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (launch_attn_combine(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims)
+{
+    if (validate_accept_dims(dims) != ADASPEC_OK) return 0;
+    return make_accept_plan(*dims).total_bytes;
+}
+
+int adaspec_accept(const void *target_logits, const void *draft_probs,
+                   const int32_t *draft_tokens, const float *uniforms,
+                   const int32_t *spec_lens, const float *temperature,
+                   int32_t *out_tokens, int32_t *out_accept_len,
+                   const adaspec_accept_dims *dims,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_accept_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    if (dims->batch == 0) return ADASPEC_OK;
+    if (!target_logits || !uniforms || !spec_lens || !temperature || !out_tokens || !out_accept_len ||
+        !workspace)
+        return ADASPEC_ERR_NULL;
+    if (dims->total_draft > 0 && (!draft_probs || !draft_tokens)) return ADASPEC_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
+    const bool fast_ok = accept_fast_path_supported(*dims, target_logits, draft_probs);
+    if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
+    const bool fast = fast_ok && dims->path != ADASPEC_PATH_VECTOR;
+    AcceptArgs a;
+    a.plan = make_accept_plan(*dims);
+    if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;
+    a.logits = target_logits; a.probs = draft_probs; a.draft_tokens = draft_tokens;
+    a.uniforms = uniforms; a.spec_lens = spec_lens; a.temperature = temperature;
+    a.out_tokens = out_tokens; a.out_accept_len = out_accept_len;
+    a.dims = *dims; a.ws = static_cast<char *>(workspace);
+    a.stream = static_cast<hipStream_t>(stream);
+
+    if (launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    hipError_t e = fast ? launch_accept_fast(a) : launch_accept_vector(a);
+    if (e != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (launch_accept_emit(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_lens,
+                                const int32_t *spec_lens, const adaspec_attn_dims *dims,
+                                int32_t *err_flags, void *stream)
+{
+    int rc = validate_attn_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    if (!block_table || !ctx_lens || !spec_lens || !err_flags) return ADASPEC_ERR_NULL;
+    if (launch_check_ragged(block_table, ctx_lens, spec_lens, *dims, err_flags,
+                            static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+int adaspec_set_timing_events(int which, void *start_event, void *stop_event)
+{
+    if (which < 0 || which > 1) return ADASPEC_ERR_DIM;
+    g_ev_start[which] = static_cast<hipEvent_t>(start_event);
+    g_ev_stop[which] = static_cast<hipEvent_t>(stop_event);
+    return ADASPEC_OK;
+}
+
+const char *adaspec_status_string(int status)
+{
+    switch (status) {
+    case ADASPEC_OK: return "ok";
+    case ADASPEC_ERR_NULL: return "a required pointer is NULL";
+    case ADASPEC_ERR_DIM: return "a dimension is out of range or inconsistent";
+    case ADASPEC_ERR_DTYPE: return "unknown or unsupported element type";
+    case ADASPEC_ERR_ALIGN: return "pointer or stride is not aligned as required";
+    case ADASPEC_ERR_WORKSPACE: return "workspace too small";
+    case ADASPEC_ERR_UNSUPPORTED: return "shape not supported by the requested kernel path";
+    case ADASPEC_ERR_HIP: return "a HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+int adaspec_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,139 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before enqueuing anything.
+Every call below fails validation, so no kernel is ever launched from this file."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2503_05096_amd as pkg
+from paper_2503_05096_amd.binding import AttnDims, AcceptDims, EXPORTS, F32, BF16
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "adaspec.h")
+PTR = 0x10000   # non-null, 256-byte aligned, never dereferenced: validation fails first
+
+
+def test_header_symbols_are_exported():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(adaspec_[a-z_]+)\s*\(", text))
+    assert names == set(EXPORTS)
+    L = pkg.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert pkg.version() >= 100
+    assert pkg.status_string(0) == "ok" and "NULL" in pkg.status_string(-1)
+
+
+def _attn_dims(**kw):
+    base = dict(batch=2, total_q=5, max_spec_len=3, n_q_heads=8, n_kv_heads=2, head_dim=128, page_size=16,
+                num_pages=64, max_pages_per_req=8, dtype=BF16, out_dtype=BF16, path=0, scale=0.0)
+    base.update(kw)
+    return AttnDims(**base)
+
+
+def _accept_dims(**kw):
+    base = dict(batch=2, total_q=5, total_draft=3, max_spec_len=3, vocab=1024, logits_dtype=BF16,
+                probs_dtype=BF16, out_stride=4, logits_row_stride=1024, probs_row_stride=1024, path=0,
+                reserved=0)
+    base.update(kw)
+    return AcceptDims(**base)
+
+
+def _call_attn(dims, ptrs=None, ws=PTR, ws_bytes=1 << 40):
+    p = [PTR] * 7 if ptrs is None else ptrs
+    return pkg.lib().adaspec_verify_attn(*p, C.byref(dims), ws, ws_bytes, None)
+
+
+def _call_accept(dims, ptrs=None, ws=PTR, ws_bytes=1 << 40):
+    p = [PTR] * 8 if ptrs is None else ptrs
+    return pkg.lib().adaspec_accept(*p, C.byref(dims), ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=-1), -2), (dict(total_q=1), -2), (dict(total_q=9), -2), (dict(n_kv_heads=3), -2),
+    (dict(n_q_heads=0), -2), (dict(num_pages=0), -2), (dict(max_pages_per_req=0), -2),
+    (dict(dtype=7), -3), (dict(out_dtype=1), -3), (dict(page_size=32), -6), (dict(head_dim=100), -6),
+    (dict(head_dim=512), -6), (dict(path=5), -2), (dict(scale=-1.0), -2), (dict(max_spec_len=-1), -2),
+])
+def test_attn_rejects_bad_dims(kw, code):
+    d = _attn_dims(**kw)
+    assert _call_attn(d) == code
+    assert pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(d)) == 0
+
+
+def test_attn_rejects_null_misaligned_and_small_workspace():
+    d = _attn_dims()
+    need = pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(d))
+    assert need > 0 and need % 256 == 0
+    assert pkg.lib().adaspec_verify_attn(*[PTR] * 7, None, PTR, need, None) == -1
+    for k in range(7):
+        p = [PTR] * 7
+        p[k] = None
+        assert _call_attn(d, p) == -1
+    assert _call_attn(d, ws=None) == -1
+    for k in (0, 1, 2, 6):
+        p = [PTR] * 7
+        p[k] = PTR + 8
+        assert _call_attn(d, p) == -4
+    assert _call_attn(d, ws=PTR + 64) == -4
+    assert _call_attn(d, ws_bytes=need - 1) == -5
+    # out_dtype may be the input type or fp32, nothing else
+    assert pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(_attn_dims(out_dtype=F32))) > 0
+
+
+def test_attn_workspace_grows_with_the_problem():
+    f = lambda **kw: pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(_attn_dims(**kw)))
+    assert f(batch=4, total_q=10) > f()
+    assert f(max_pages_per_req=512) > f()
+    assert f(max_spec_len=7) > f()
+
+
+def test_empty_batch_is_a_no_op():
+    assert _call_attn(_attn_dims(batch=0, total_q=0), [None] * 7, ws=None, ws_bytes=0) == 0
+    assert _call_accept(_accept_dims(batch=0, total_q=0, total_draft=0), [None] * 8, ws=None, ws_bytes=0) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(batch=-2), -2), (dict(total_draft=4), -2), (dict(vocab=0), -2), (dict(logits_dtype=9), -3),
+    (dict(probs_dtype=-1), -3), (dict(logits_row_stride=1000), -2), (dict(probs_row_stride=8), -2),
+    (dict(out_stride=3), -2), (dict(path=-1), -2), (dict(total_q=12, total_draft=10), -2),
+])
+def test_accept_rejects_bad_dims(kw, code):
+    d = _accept_dims(**kw)
+    assert _call_accept(d) == code
+    assert pkg.lib().adaspec_accept_workspace_bytes(C.byref(d)) == 0
+
+
+def test_accept_rejects_null_and_small_workspace():
+    d = _accept_dims()
+    need = pkg.lib().adaspec_accept_workspace_bytes(C.byref(d))
+    assert need > 0
+    for k in range(8):
+        p = [PTR] * 8
+        p[k] = None
+        assert _call_accept(d, p) == -1
+    assert _call_accept(d, ws=None) == -1
+    assert _call_accept(d, ws=PTR + 16) == -4
+    assert _call_accept(d, ws_bytes=need - 1) == -5
+    # the register-resident path refuses shapes it cannot hold
+    assert _call_accept(_accept_dims(path=2, logits_dtype=F32)) == -6
+    assert _call_accept(_accept_dims(path=2, vocab=1001, logits_row_stride=1001, probs_row_stride=1001)) == -6
+
+
+def test_misc_entry_points_validate():
+    L = pkg.lib()
+    assert L.adaspec_set_timing_events(2, None, None) == -2
+    assert L.adaspec_set_timing_events(0, None, None) == 0
+    assert L.adaspec_check_ragged_inputs(None, PTR, PTR, C.byref(_attn_dims()), PTR, None) == -1
+    assert L.adaspec_check_ragged_inputs(PTR, PTR, PTR, C.byref(_attn_dims(batch=-1)), PTR, None) == -2
+    assert "unknown" in pkg.status_string(-99)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2503_05096_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.lib()

@@ -1,0 +1,228 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, on the
+same seeded inputs, through the C ABI.  Tolerances:
+
+  attention   max |gpu - oracle_f64| <= 2e-3 on the fp32 accumulator output
+              (out_dtype = fp32); the 16-bit output must be that accumulator
+              rounded once to nearest-even, bit for bit.
+  acceptance  tokens and accept lengths bit-exact except counted near-ties
+              (see tests/harness.py); greedy rows have no tolerance at all.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from tests.harness import compare_accept, compare_attention, to_device
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+F32 = 0
+
+
+def _say(msg):
+    print(f"[case] {msg}", file=sys.stderr, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):                      # keep the measured errors / near-tie counts of the run
+        with open(os.path.join(d, "parity_report.log"), "a") as f:
+            f.write(msg + "\n")
+
+
+def _round_like(x32, dtype):
+    import torch
+    return x32.to({"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[dtype])
+
+
+def check_attention(st, oracle, pkg, path="auto", tol=ATTN_TOL):
+    import torch
+    dev = to_device(st, acceptance=False)
+    ref, ref_r = oracle.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens,
+                                    st.spec_lens, dtype=st.dtype)
+    kw = dict(max_spec_len=st.max_spec_len, path=path)
+    _say(f"attn {st.name} path={path} B={st.batch} TQ={st.total_q} dtype={st.dtype} out=f32")
+    acc = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                          out_dtype=F32, **kw)
+    torch.cuda.synchronize()
+    rep = compare_attention(acc, ref, None, st.dtype)
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= tol, rep
+    _say(f"attn {st.name} path={path} out={st.dtype}")
+    out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out, _round_like(acc, st.dtype)), "stored output is not RNE(accumulator)"
+    rep2 = compare_attention(out, ref, ref_r, st.dtype)
+    rep.update(max_abs_rounded_vs_f64=rep2["max_abs_vs_f64"],
+               frac_bit_equal_rounded=rep2["frac_bit_equal_rounded"])
+    # determinism: a second run is bit-identical
+    out2 = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    _say(f"attn {st.name} ok {rep}")
+    return rep
+
+
+def check_accept(st, oracle, pkg, path="auto", out_stride=None, max_near_tie_frac=0.05):
+    import torch
+    dev = to_device(st, attention=False)
+    _say(f"accept {st.name} path={path} B={st.batch} TQ={st.total_q} V={st.vocab}")
+    toks, alen = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms,
+                            dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len,
+                            out_stride=out_stride, path=path)
+    torch.cuda.synchronize()
+    rep = compare_accept(st, toks.cpu().numpy(), alen.cpu().numpy(), oracle, out_stride=out_stride)
+    _say(f"accept {st.name} {({k: v for k, v in rep.items() if k != 'details'})}")
+    assert rep["hard_mismatches"] == 0, rep["details"][:5]
+    assert rep["ratio_near_ties"] + rep["cdf_near_ties"] <= max(2, max_near_tie_frac * st.batch), rep
+    toks2, alen2 = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms,
+                              dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len,
+                              out_stride=out_stride, path=path)
+    torch.cuda.synchronize()
+    assert torch.equal(toks, toks2) and torch.equal(alen, alen2)
+    return rep
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2503_05096_amd as p
+    return p
+
+
+# ------------------------------------------------------------------ the five configs
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_config_attention(cfg, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, acceptance=False)
+    check_attention(st, oracle_mod, pkg)
+
+
+@pytest.mark.parametrize("cfg,greedy", [(1, False), (2, False), (3, False), (4, False), (4, True), (5, False)])
+def test_config_accept(cfg, greedy, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, greedy=greedy, attention=False)
+    check_accept(st, oracle_mod, pkg)
+
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_config_attention_vector_path(cfg, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, acceptance=False, batch=16)
+    check_attention(st, oracle_mod, pkg, path="vector")
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_config_accept_vector_path(cfg, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, attention=False, batch=24)
+    check_accept(st, oracle_mod, pkg, path="vector")
+
+
+# ------------------------------------------------------------------ adversarial inputs
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_adversarial_sharp_softmax_and_planted_ties(cfg, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, batch=24, sharp_key=True, planted_ties=True)
+    check_attention(st, oracle_mod, pkg)
+    check_accept(st, oracle_mod, pkg)
+    import copy
+    g = copy.copy(st)
+    g.temperature = np.zeros_like(st.temperature)      # all greedy on tied maxima: lowest index must win
+    check_accept(g, oracle_mod, pkg)
+
+
+# ------------------------------------------------------------------ edge cases
+EDGE_SHAPES = [
+    # ctx_lens, spec_lens, Hq, Hkv, d, dtype
+    ([1], [0], 4, 4, 64, "f32"),                      # one token, plain decode
+    ([5, 9, 3], [4, 8, 2], 8, 2, 128, "bf16"),        # context == only the new tokens (+ tiny history)
+    ([16, 17, 31, 32, 33], [0, 1, 2, 3, 4], 8, 8, 128, "f16"),      # page boundaries
+    ([300, 1, 1025, 64], [6, 0, 3, 0], 32, 8, 128, "bf16"),         # several splits and a one-token request
+    ([257, 511, 513], [1, 0, 8], 16, 2, 64, "bf16"),  # GQA 8, 72 query rows, d = 64
+    ([100, 200], [2, 1], 6, 3, 80, "f16"),            # head_dim the matrix-core path does not take
+    ([2100], [5], 64, 8, 128, "bf16"),                # one long request: many splits, 48 rows
+]
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES, ids=lambda s: f"L{s[0]}-k{s[1]}-{s[2]}x{s[3]}x{s[4]}-{s[5]}")
+def test_attention_edge_shapes(shape, oracle_mod, pkg):
+    ctx, spec, hq, hkv, d, dt = shape
+    st = W.make_custom_step(1234, ctx_lens=ctx, spec_lens=spec, n_q_heads=hq, n_kv_heads=hkv, head_dim=d,
+                            dtype=dt, acceptance=False, name=f"edge-{dt}")
+    check_attention(st, oracle_mod, pkg)
+
+
+def test_attention_max_spec_len_larger_than_used(oracle_mod, pkg):
+    import torch
+    st = W.make_custom_step(77, ctx_lens=[90, 40], spec_lens=[2, 0], n_q_heads=8, n_kv_heads=2, head_dim=128,
+                            dtype="bf16", acceptance=False)
+    dev = to_device(st, acceptance=False)
+    ref, _ = oracle_mod.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                                    dtype=st.dtype)
+    _say("attn max_spec_len=8 while max k = 2")
+    out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                          max_spec_len=8, out_dtype=F32)
+    torch.cuda.synchronize()
+    assert compare_attention(out, ref, None, "bf16")["max_abs_vs_f64"] <= ATTN_TOL
+
+
+def test_attention_custom_scale(oracle_mod, pkg):
+    import torch
+    st = W.make_custom_step(78, ctx_lens=[130], spec_lens=[3], n_q_heads=8, n_kv_heads=8, head_dim=64,
+                            dtype="f32", acceptance=False)
+    dev = to_device(st, acceptance=False)
+    ref, _ = oracle_mod.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                                    dtype=st.dtype, scale=0.05)
+    _say("attn custom scale")
+    out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                          max_spec_len=3, scale=0.05)
+    torch.cuda.synchronize()
+    assert compare_attention(out, ref, None, "f32")["max_abs_vs_f64"] <= 1e-5
+
+
+ACCEPT_EDGES = [
+    # spec_lens, vocab, logits dtype, temperatures
+    ([0, 0, 0], 1000, "f32", 1.0),                    # plain decode only
+    ([3, 1, 0, 5], 8, "f32", [1.0, 0.5, 2.0, 1.0]),   # tiny vocabulary
+    ([2, 4], 1001, "bf16", 0.7),                      # vocab not a multiple of 8
+    ([8, 0, 3], 32000, "bf16", [0.0, 0.0, 0.0]),      # all greedy
+    ([1, 2, 3, 4], 4104, "f16", [0.0, 0.3, 1.0, 1.5]),  # fp16 logits, mixed temperatures
+    ([6], 131072, "bf16", 1.0),                       # largest vocabulary of the register-resident path
+    ([2], 131080, "bf16", 1.0),                       # just beyond it
+]
+
+
+@pytest.mark.parametrize("shape", ACCEPT_EDGES, ids=lambda s: f"k{s[0]}-V{s[1]}-{s[2]}")
+def test_accept_edge_shapes(shape, oracle_mod, pkg):
+    spec, V, dt, T = shape
+    st = W.make_custom_step(4321, ctx_lens=[64] * len(spec), spec_lens=spec, vocab=V, logits_dtype=dt,
+                            temperature=T, attention=False, logits_sigma=3.0, noise_sigma=1.5,
+                            draft_temp=1.2, name=f"edge-{dt}")
+    check_accept(st, oracle_mod, pkg)
+    check_accept(st, oracle_mod, pkg, out_stride=st.max_spec_len + 4)
+
+
+def test_accept_p_equals_q_accepts_everything(oracle_mod, pkg):
+    import torch
+    V, B, k = 4096, 16, 4
+    rng = np.random.default_rng(5)
+    st = W.make_custom_step(99, ctx_lens=[64] * B, spec_lens=[k] * B, vocab=V, logits_dtype="f32",
+                            temperature=1.0, attention=False)
+    st.target_logits[:] = 0.25                       # p = 1/V exactly
+    st.draft_probs[:] = 1.0 / V
+    st.draft_tokens[:] = rng.integers(0, V, size=B * k)
+    st.uniforms[::2, 0] = np.float32(1.0 - 2.0 ** -24)
+    rep = check_accept(st, oracle_mod, pkg)
+    assert rep["oracle_mean_accept_len"] == k and rep["exact"] + rep["cdf_near_ties"] == B
+
+
+def test_ragged_input_check(pkg):
+    import torch
+    st = W.make_custom_step(5, ctx_lens=[40, 17], spec_lens=[2, 0], n_q_heads=4, n_kv_heads=2, head_dim=64,
+                            dtype="bf16", acceptance=False)
+    dev = to_device(st, acceptance=False)
+    dims = pkg.binding.attn_dims(dev.q, dev.k_pages, dev.block_table, max_spec_len=2)
+    _say("ragged check")
+    assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, dev.spec_lens, dims) == 0
+    bad = dev.ctx_lens.clone(); bad[0] = 2
+    assert pkg.check_ragged_inputs(dev.block_table, bad, dev.spec_lens, dims) & 2
+    bt = dev.block_table.clone(); bt[0, 0] = st.num_pages
+    assert pkg.check_ragged_inputs(bt, dev.ctx_lens, dev.spec_lens, dims) & 4
+    sp = dev.spec_lens.clone(); sp[1] = 1
+    assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, sp, dims) & 8
+    sp[1] = 9
+    assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, sp, dims) & 1
