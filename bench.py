@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of one ragged verification step (attention + acceptance) on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+adaspec_verify_attn (one attention layer) followed by adaspec_accept, with all
+inputs resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (the library records them around its main kernel)."""
+
+    def __init__(self, n: int):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.start, self.stop = [], []
+        for _ in range(n):
+            for lst in (self.start, self.stop):
+                ev = C.c_void_p()
+                assert self.hip.hipEventCreate(C.byref(ev)) == 0
+                lst.append(ev)
+
+    def elapsed_ms(self, k: int) -> float:
+        ms = C.c_float()
+        assert self.hip.hipEventSynchronize(self.stop[k]) == 0
+        assert self.hip.hipEventElapsedTime(C.byref(ms), self.start[k], self.stop[k]) == 0
+        return float(ms.value)
+
+    def close(self):
+        for ev in self.start + self.stop:
+            self.hip.hipEventDestroy(ev)
+
+
+def cpu_baseline(st) -> dict:
+    """The oracle, as it stands, on this machine's host cores, over the same workload."""
+    import oracle
+    oracle.build(force=False)
+    t0 = time.perf_counter()
+    oracle.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                       dtype=st.dtype, want_rounded=False)
+    t1 = time.perf_counter()
+    oracle.accept(st.target_logits, st.draft_probs, st.draft_tokens, st.uniforms, st.spec_lens,
+                  st.temperature, logits_dtype=st.logits_dtype, probs_dtype=st.probs_dtype,
+                  want_row_info=False)
+    t2 = time.perf_counter()
+    return {"value": st.total_q / (t2 - t0), "unit": "verified query-tokens/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"1 full step of {st.name} (all {st.batch} requests, one attention layer + acceptance; "
+                      f"the sequential oracle stops at each request's first rejection); "
+                      f"attention {t1 - t0:.2f} s, acceptance {t2 - t1:.2f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4g", "cfg5"])
+    ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as W
+    import paper_2503_05096_amd as pkg
+    from tests.harness import to_device
+
+    cfg = int(args.workload[3])
+    st = W.make_verify_step(cfg, greedy=args.workload.endswith("g"), poison=False)
+    nbytes = W.algorithmic_bytes(st)
+    torch.cuda.set_device(0)
+    dev = to_device(st, "cuda:0")
+    stream = torch.cuda.Stream()
+    kmax = st.max_spec_len
+    B = st.batch
+    out = torch.empty(dev.q.shape, dtype=dev.q.dtype, device="cuda:0")
+    toks = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
+    alen = torch.empty((B,), dtype=torch.int32, device="cuda:0")
+    # separate workspaces so the two calls never alias
+    a_dims = pkg.binding.attn_dims(dev.q, dev.k_pages, dev.block_table, max_spec_len=kmax, path=args.path)
+    ws_attn = torch.empty(max(pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(a_dims)), 256),
+                          dtype=torch.uint8, device="cuda:0")
+    ws_acc = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+
+    def step():
+        pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                        out, max_spec_len=kmax, path=args.path, workspace=ws_attn, stream=stream)
+        pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens,
+                   dev.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
+                   path=args.path, workspace=ws_acc, stream=stream)
+
+    ev_attn, ev_acc = HipEvents(args.steps), HipEvents(args.steps)
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            pkg.set_timing_events(0, ev_attn.start[k], ev_attn.stop[k])
+            pkg.set_timing_events(1, ev_acc.start[k], ev_acc.stop[k])
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    pkg.set_timing_events(0, None, None)
+    pkg.set_timing_events(1, None, None)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    attn_ms = sum(ev_attn.elapsed_ms(k) for k in range(args.steps)) / args.steps
+    acc_ms = sum(ev_acc.elapsed_ms(k) for k in range(args.steps)) / args.steps
+    ev_attn.close(); ev_acc.close()
+
+    def gbs(nb, ms):
+        return nb / (ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{args.workload}:{args.path}")
+    rec = {
+        "metric": "verified query-tokens/sec per verify step (attn+accept); achieved HBM GB/s",
+        "value": st.total_q / (ms_step * 1e-3),
+        "unit": "verified query-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": st.dtype if st.dtype != "f32" else "f32", "data": "synthetic",
+        "config": {"workload": st.name, "batch": B, "total_query_tokens": st.total_q,
+                   "total_draft_tokens": st.total_draft, "sum_ctx_tokens": int(st.ctx_lens.sum()),
+                   "n_q_heads": st.n_q_heads, "n_kv_heads": st.n_kv_heads, "head_dim": st.head_dim,
+                   "vocab": st.vocab, "page_size": st.page_size, "kernel_path": args.path,
+                   "step": "1 attention layer + 1 acceptance"},
+        "roofline": {"bound": "hbm", "kernel": "verify-attention main kernel",
+                     "achieved": gbs(nbytes["attn"], attn_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs(nbytes["attn"], attn_ms) / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes": nbytes["attn"], "avg_kernel_ms": attn_ms},
+        "roofline_accept": {"bound": "hbm", "kernel": "acceptance main kernel",
+                            "achieved": gbs(nbytes["accept"], acc_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": gbs(nbytes["accept"], acc_ms) / HBM_PEAK_GBS,
+                            "algorithmic_bytes": nbytes["accept"], "avg_kernel_ms": acc_ms},
+        "hbm_step": {"achieved": gbs(nbytes["total"], ms_step), "frac": gbs(nbytes["total"], ms_step) / HBM_PEAK_GBS,
+                     "unit": "GB/s", "algorithmic_bytes": nbytes["total"],
+                     "note": "all algorithmic bytes of the step over the whole step time, launches included"},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(st)
+    print(json.dumps(rec))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,7 +1,405 @@
-// Matrix-core verification attention (placeholder until the kernel lands).
+// Matrix-core verification attention for gfx950: 16-bit K/V/Q, head_dim 128.
+//
+// Work unit = (work item = request x KV split, kv head, group of up to 16*RT
+// query rows).  A workgroup of 4 wavefronts takes one unit; wavefront w streams
+// the 32-token blocks w, w+4, ... of the split, keeping the online-softmax state
+// of ALL rows of the unit (the n_i*G rows that share this kv head) in registers,
+// so every K and V byte is fetched from HBM once per unit.  The four partial
+// states are merged through LDS at the end.
+//
+// Everything is computed transposed so that no operand ever needs a shuffle:
+//   S^T[token][row] = K[token][:] . Q[row][:]      A = K (straight from global), B = Q^T
+//   O^T[d][row]    += V^T[d][token] P^T[token][row]  A = V^T (through LDS),       B = P^T
+// With v_mfma_f32_16x16x32 the accumulator lane (g = lane/16, n = lane%16) holds
+// S^T[4g..4g+3][n]; those 2x4 values per lane (two 16-token tiles) are exactly the
+// 8 k-slots lane (g, n) must supply as B operand of the second product, so P never
+// leaves the registers.  The k-slot order (g, e) <-> token 16*(e/4) + 4g + e%4 is
+// then imposed on V^T: V rows are loaded coalesced (each lane: 4 tokens x 8
+// channels per page), transposed 4x8 in registers with byte permutes and written
+// to a wavefront-private 8 KB LDS tile laid out so that both the 16-byte writes
+// and the 16-byte operand reads are bank-conflict free.
 #include "adaspec_internal.h"
+#include "device_utils.h"
 
 namespace adaspec {
-bool attn_fast_path_supported(const adaspec_attn_dims &) { return false; }
-hipError_t launch_attn_mfma(const AttnArgs &) { return hipErrorNotSupported; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;                 // head_dim
+constexpr int kBlk = 32;                // tokens per block (two pages)
+constexpr int kWaves = 4;
+constexpr int kORowStride = 132;        // floats per row of the merge buffer (padded: conflict-free b128)
+constexpr float kNegBig = -1.0e30f;     // "no token seen yet": finite, so differences never give NaN
+
+template <class T> struct Mma;
+template <> struct Mma<BF16> {
+    // bf16 keeps 8 significant bits: a softmax weight rounded to it is off by up to 2^-9 relative,
+    // which with a handful of dominant tokens reaches the 2e-3 output tolerance.  The weights are
+    // therefore fed to the matrix core as hi + lo (two bf16 values, 16 significant bits).
+    static constexpr bool kSplitP = true;
+    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));   // v_cvt_pk_bf16_f32, RNE
+    }
+};
+template <> struct Mma<F16> {
+    static constexpr bool kSplitP = false;       // fp16 keeps 11 bits: 2^-12 relative is enough
+    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));    // v_cvt_pk_f16_f32, RNE
+    }
+};
+
+__device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+template <class T, int RT>
+__global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
+    const char *__restrict__ q, const char *__restrict__ k_pages, const char *__restrict__ v_pages,
+    const int32_t *__restrict__ block_table, const int32_t *__restrict__ ctx_lens,
+    const int32_t *__restrict__ spec_lens, void *__restrict__ out, int32_t *__restrict__ header,
+    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ split_base,
+    const int32_t *__restrict__ item_req, float *__restrict__ part_ml, float *__restrict__ part_o,
+    int Hq, int Hkv, int max_pages_per_req, int max_rows, int n_row_groups, float scale_log2,
+    int out_dtype)
+{
+    constexpr int kRows = 16 * RT;
+    constexpr int kRegion = 8192;                                   // one wavefront's V^T tile
+    constexpr int kMerge = kRows * kORowStride * 4;                 // the [rows][d] fp32 merge buffer
+    constexpr int kSmem = kWaves * kRegion > kMerge ? kWaves * kRegion : kMerge;
+    __shared__ __attribute__((aligned(16))) char smem[kSmem];
+    __shared__ float s_m[kWaves][kRows], s_l[kWaves][kRows], s_mstar[kRows];
+    __shared__ int s_ticket;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int g = lane >> 4, n16 = lane & 15;
+    const int G = Hq / Hkv;
+    const int total_units = header[0] * Hkv * n_row_groups;
+    char *my_lds = smem + wv * kRegion;
+
+    // LDS byte offsets of the V^T tile (unit = 16 bytes = the 8 k-slots of one channel for one lane group):
+    //   unit(d = 8c + dd, grp) = 16 * (4 dd + grp) + ((c + 2 dd) & 15)
+    // writer lane = (tq = g, c = n16) for dd = 0..7; reader lane = (g, m = n16) for channel 16 dt + m.
+    uint32_t wr_off[8], rd_off[8];
+#pragma unroll
+    for (int dd = 0; dd < 8; ++dd) wr_off[dd] = 16u * (16u * (4u * dd + g) + ((n16 + 2u * dd) & 15u));
+    {
+        const uint32_t h = n16 >> 3, ddp = n16 & 7;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            rd_off[dt] = 16u * (16u * (4u * ddp + g) + ((2u * dt + h + 2u * ddp) & 15u));
+    }
+
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) s_ticket = atomicAdd(&header[1], 1);
+        __syncthreads();
+        const int ticket = s_ticket;
+        if (ticket >= total_units) break;
+        const int rg = ticket % n_row_groups;
+        const int gkv = (ticket / n_row_groups) % Hkv;
+        const int item = ticket / (n_row_groups * Hkv);
+        const int i = item_req[item];
+        const int s0 = split_base[i], ns = split_base[i + 1] - s0, sp = item - s0;
+        const int L = ctx_lens[i], n = spec_lens[i] + 1;
+        const int rows = n * G, r0 = rg * kRows;
+        if (r0 >= rows) continue;
+        const int slen = split_len_of(L, ns, kBlk);
+        const int t0 = sp * slen, t1 = min(L, t0 + slen);
+        const int nblk = (t1 - t0 + kBlk - 1) / kBlk;
+        const int64_t qrow0 = cu_q[i];
+        const int32_t *bt = block_table + (int64_t)i * max_pages_per_req;
+        const int64_t head_bytes = (int64_t)16 * kD * 2;               // one (page, head) block
+        const int first_masked = L - n + 1;                            // tokens >= this are hidden from some row
+
+        // ---- Q^T operands and per-row visibility limits ---------------------------------
+        uint4 qop[RT][4];
+        int pos[RT];
+#pragma unroll
+        for (int nt = 0; nt < RT; ++nt) {
+            const int row = r0 + 16 * nt + n16;
+            const bool ok = row < rows;
+            pos[nt] = ok ? (L - n + row / G) : -1;
+            const char *qp = q + (((qrow0 + (ok ? row / G : 0)) * Hq + gkv * G + (ok ? row % G : 0)) * kD) * 2 +
+                             16 * g;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) qop[nt][s] = ok ? ld16(qp + 64 * s) : make_uint4(0, 0, 0, 0);
+        }
+
+        float m[RT], lsum[RT];
+        f32x4 o[RT][8];
+#pragma unroll
+        for (int nt = 0; nt < RT; ++nt) {
+            m[nt] = kNegBig; lsum[nt] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+
+        // K operand: lane (g, m) <- token 16 mt + m, channels 32 s + 8 g .. +7
+        // V raw:     lane (tq = g, c = n16) <- token 16 pg + 4 tq + i, channels 8 c .. 8 c + 7
+        uint4 kreg[2][4], vreg[2][4];
+        const uint32_t k_lane_off = n16 * (kD * 2) + 16 * g;
+        const uint32_t v_lane_off = (4 * g) * (kD * 2) + 16 * n16;
+
+        auto load_block = [&](int bi, bool want_k, bool want_v) {
+            const int tb = t0 + bi * kBlk;
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg) {
+                const bool have = tb + 16 * pg < t1;                   // wave-uniform
+                if (have) {
+                    const int64_t page = bt[(tb >> 4) + pg];
+                    const int64_t base = (page * Hkv + gkv) * head_bytes;
+                    if (want_k) {
+                        const char *kp = k_pages + base + k_lane_off;
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) kreg[pg][s] = ld16(kp + 64 * s);
+                    }
+                    if (want_v) {
+                        const char *vp = v_pages + base + v_lane_off;
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii) vreg[pg][ii] = ld16(vp + ii * (kD * 2));
+                    }
+                } else {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        if (want_k) kreg[pg][s] = make_uint4(0, 0, 0, 0);
+                        if (want_v) vreg[pg][s] = make_uint4(0, 0, 0, 0);
+                    }
+                }
+            }
+        };
+
+        int bi = wv;
+        if (bi < nblk) load_block(bi, true, true);
+
+        for (; bi < nblk; bi += kWaves) {
+            const int tb = t0 + bi * kBlk;
+            const bool has_next = bi + kWaves < nblk;
+
+            // ---- S^T = K Q^T ------------------------------------------------------------
+            f32x4 sacc[RT][2];
+#pragma unroll
+            for (int nt = 0; nt < RT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) acc = Mma<T>::run(kreg[mt][s], qop[nt][s], acc);
+                    sacc[nt][mt] = acc;
+                }
+            if (has_next) load_block(bi + kWaves, true, false);
+
+            // ---- online softmax (per lane: row n16 of each row tile, 8 of the 32 tokens) ----
+            const bool need_mask = (tb + kBlk > first_masked) || (tb + kBlk > t1);
+            uint4 pop[RT], pop_lo[RT];
+#pragma unroll
+            for (int nt = 0; nt < RT; ++nt) {
+                float sv[8];
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sv[4 * mt + r] = sacc[nt][mt][r];
+                if (need_mask) {
+                    const int lim = min(pos[nt], t1 - 1);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int t = tb + 16 * (e >> 2) + 4 * g + (e & 3);
+                        sv[e] = (t <= lim) ? sv[e] : -INFINITY;
+                    }
+                }
+                float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                                 fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+                const float m_new = fmaxf(m[nt], mx * scale_log2);
+                const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+                m[nt] = m_new;
+                float p[8], psum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], scale_log2, -m_new));
+                    psum += p[e];
+                }
+                lsum[nt] = lsum[nt] * alpha + psum;
+                pop[nt] = make_uint4(Mma<T>::pack2(p[0], p[1]), Mma<T>::pack2(p[2], p[3]),
+                                     Mma<T>::pack2(p[4], p[5]), Mma<T>::pack2(p[6], p[7]));
+                if constexpr (Mma<T>::kSplitP) {
+                    const uint32_t *hi = &pop[nt].x;
+                    uint32_t lo[4];
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        lo[w] = Mma<T>::pack2(p[2 * w] - __uint_as_float(hi[w] << 16),
+                                              p[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u));
+                    pop_lo[nt] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                }
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) o[nt][dt] *= alpha;
+                }
+            }
+
+            // ---- V^T tile: sanitise the tail, transpose 4x8 in registers, write to LDS ----
+            if (tb + kBlk > L) {                       // the request's last, partial block
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii)
+                        if (tb + 16 * pg + 4 * g + ii >= L) vreg[pg][ii] = make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t a0 = (&vreg[0][0].x)[w], a1 = (&vreg[0][1].x)[w];
+                const uint32_t a2 = (&vreg[0][2].x)[w], a3 = (&vreg[0][3].x)[w];
+                const uint32_t b0 = (&vreg[1][0].x)[w], b1 = (&vreg[1][1].x)[w];
+                const uint32_t b2 = (&vreg[1][2].x)[w], b3 = (&vreg[1][3].x)[w];
+                uint4 even = make_uint4(__builtin_amdgcn_perm(a1, a0, 0x05040100u),
+                                        __builtin_amdgcn_perm(a3, a2, 0x05040100u),
+                                        __builtin_amdgcn_perm(b1, b0, 0x05040100u),
+                                        __builtin_amdgcn_perm(b3, b2, 0x05040100u));
+                uint4 odd = make_uint4(__builtin_amdgcn_perm(a1, a0, 0x07060302u),
+                                       __builtin_amdgcn_perm(a3, a2, 0x07060302u),
+                                       __builtin_amdgcn_perm(b1, b0, 0x07060302u),
+                                       __builtin_amdgcn_perm(b3, b2, 0x07060302u));
+                *reinterpret_cast<uint4 *>(my_lds + wr_off[2 * w]) = even;
+                *reinterpret_cast<uint4 *>(my_lds + wr_off[2 * w + 1]) = odd;
+            }
+            if (has_next) load_block(bi + kWaves, false, true);
+
+            // ---- O^T += V^T P^T -------------------------------------------------------------
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const uint4 vt = *reinterpret_cast<const uint4 *>(my_lds + rd_off[dt]);
+#pragma unroll
+                for (int nt = 0; nt < RT; ++nt) {
+                    o[nt][dt] = Mma<T>::run(vt, pop[nt], o[nt][dt]);
+                    if constexpr (Mma<T>::kSplitP) o[nt][dt] = Mma<T>::run(vt, pop_lo[nt], o[nt][dt]);
+                }
+            }
+        }
+
+        // ---- merge the four wavefronts' states through LDS --------------------------------
+        // m* = max over wavefronts, each state rescaled by 2^(m - m*); the O tiles are summed
+        // into one [rows][d] fp32 buffer (aliasing the V^T tiles) one wavefront after another.
+#pragma unroll
+        for (int nt = 0; nt < RT; ++nt) {
+            lsum[nt] += __shfl_xor(lsum[nt], 16, kWave);
+            lsum[nt] += __shfl_xor(lsum[nt], 32, kWave);
+            if (g == 0) s_m[wv][16 * nt + n16] = m[nt];
+        }
+        __syncthreads();                                   // also: every wave is done with its V^T tile
+        float *obuf = reinterpret_cast<float *>(smem);
+        float fsc[RT];
+#pragma unroll
+        for (int nt = 0; nt < RT; ++nt) {
+            const int rl = 16 * nt + n16;
+            float ms = s_m[0][rl];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) ms = fmaxf(ms, s_m[w][rl]);
+            fsc[nt] = __builtin_amdgcn_exp2f(m[nt] - ms);
+            if (g == 0) {
+                s_l[wv][rl] = lsum[nt] * fsc[nt];
+                if (wv == 0) s_mstar[rl] = ms;
+            }
+        }
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            if (wv == w) {
+#pragma unroll
+                for (int nt = 0; nt < RT; ++nt)
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) {
+                        f32x4 *dst = reinterpret_cast<f32x4 *>(obuf + (16 * nt + n16) * kORowStride +
+                                                               16 * dt + 4 * g);
+                        f32x4 v = o[nt][dt] * fsc[nt];
+                        if (w > 0) v += *dst;
+                        *dst = v;
+                    }
+            }
+            __syncthreads();
+        }
+        // 256 threads: 16*RT rows x 32 float4 columns
+#pragma unroll
+        for (int it = 0; it < 2 * RT; ++it) {
+            const int idx = tid + 256 * it;
+            const int rl = idx >> 5, c4 = idx & 31;
+            const int row = r0 + rl;
+            if (row >= rows) continue;
+            const f32x4 acc = *reinterpret_cast<const f32x4 *>(obuf + rl * kORowStride + 4 * c4);
+            const float ltot = (s_l[0][rl] + s_l[1][rl]) + (s_l[2][rl] + s_l[3][rl]);
+            if (ns == 1) {
+                const float inv = 1.0f / ltot;
+                const int64_t obase = ((qrow0 + row / G) * Hq + gkv * G + row % G) * (int64_t)kD + 4 * c4;
+                if (out_dtype == ADASPEC_F32) {
+                    *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + obase) = acc * inv;
+                } else {
+                    uint2 pk = make_uint2(Mma<T>::pack2(acc[0] * inv, acc[1] * inv),
+                                          Mma<T>::pack2(acc[2] * inv, acc[3] * inv));
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + obase) = pk;
+                }
+            } else {
+                const int64_t idx_row = ((int64_t)item * Hkv + gkv) * max_rows + row;
+                *reinterpret_cast<f32x4 *>(part_o + idx_row * kD + 4 * c4) = acc;
+                if (c4 == 0) {
+                    part_ml[idx_row * 2] = s_mstar[rl];
+                    part_ml[idx_row * 2 + 1] = ltot;
+                }
+            }
+        }
+    }
+}
+
+bool attn_fast_path_supported(const adaspec_attn_dims &d)
+{
+    return d.head_dim == kD && (d.dtype == ADASPEC_F16 || d.dtype == ADASPEC_BF16) && d.page_size == 16;
+}
+
+hipError_t launch_attn_mfma(const AttnArgs &a)
+{
+    const AttnPlan &p = a.plan;
+    const adaspec_attn_dims &d = a.dims;
+    int rt = ceil_div(p.max_rows, 16);
+    if (rt > 3) rt = 3;
+    const int n_row_groups = ceil_div(p.max_rows, 16 * rt);
+    const int64_t max_units = (int64_t)p.max_items * d.n_kv_heads * n_row_groups;
+    if (max_units == 0) return hipSuccess;
+    const int grid = (int)(max_units < 2048 ? max_units : 2048);
+    auto launch = [&](auto tag, auto rt_tag) {
+        using T = decltype(tag);
+        constexpr int RT = decltype(rt_tag)::value;
+        hipLaunchKernelGGL((attn_mfma_kernel<T, RT>), dim3(grid), dim3(256), 0, a.stream,
+                           (const char *)a.q, (const char *)a.k_pages, (const char *)a.v_pages,
+                           a.block_table, a.ctx_lens, a.spec_lens, a.out, (int32_t *)(a.ws + p.off_header),
+                           (const int32_t *)(a.ws + p.off_cu_q), (const int32_t *)(a.ws + p.off_split_base),
+                           (const int32_t *)(a.ws + p.off_item_req), (float *)(a.ws + p.off_part_ml),
+                           (float *)(a.ws + p.off_part_o), d.n_q_heads, d.n_kv_heads, d.max_pages_per_req,
+                           p.max_rows, n_row_groups, a.scale_log2, d.out_dtype);
+    };
+    auto with_rt = [&](auto tag) {
+        switch (rt) {
+        case 1: launch(tag, std::integral_constant<int, 1>{}); break;
+        case 2: launch(tag, std::integral_constant<int, 2>{}); break;
+        default: launch(tag, std::integral_constant<int, 3>{}); break;
+        }
+    };
+    if (d.dtype == ADASPEC_F16) with_rt(F16{});
+    else with_rt(BF16{});
+    return hipGetLastError();
+}
+
 }  // namespace adaspec
