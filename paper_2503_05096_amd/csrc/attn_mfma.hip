@@ -69,6 +69,23 @@ template <> struct Mma<F16> {
 
 __device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// K and V are read exactly once per work unit: stream them past the caches.
+__device__ __forceinline__ uint4 ld16_stream(const char *p)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+// V^T tile in LDS, in units of 16 bytes (= the 8 k-slots of one channel for one lane group):
+//   unit(d = 8c + dd, grp) = 66 dd + 16 grp + c
+// The writer lane (grp = tq, c) stores channel 8c + dd at its base + 66*16*dd bytes; the reader
+// lane (grp, m = 8h + dd') loads channel 16 dt + m = 8 (2dt + h) + dd' from its base + 32 dt bytes.
+// Within a 16-lane group both patterns hit 16 distinct 16-byte bank groups: conflict free.
+constexpr int kVtUnits = 66 * 7 + 64;
+constexpr int kVtBytes = ((kVtUnits * 16 + 255) / 256) * 256;
+
 template <class T, int RT>
 __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     const char *__restrict__ q, const char *__restrict__ k_pages, const char *__restrict__ v_pages,
@@ -80,37 +97,27 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     int out_dtype)
 {
     constexpr int kRows = 16 * RT;
-    constexpr int kRegion = 8192;                                   // one wavefront's V^T tile
     constexpr int kMerge = kRows * kORowStride * 4;                 // the [rows][d] fp32 merge buffer
-    constexpr int kSmem = kWaves * kRegion > kMerge ? kWaves * kRegion : kMerge;
+    constexpr int kSmem = kWaves * kVtBytes > kMerge ? kWaves * kVtBytes : kMerge;
     __shared__ __attribute__((aligned(16))) char smem[kSmem];
+    __shared__ __attribute__((aligned(16))) uint4 q_lds[RT * 4 * 64];   // Q^T operands, MFMA lane order
     __shared__ float s_m[kWaves][kRows], s_l[kWaves][kRows], s_mstar[kRows];
     __shared__ int s_ticket;
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave-uniform by construction
     const int g = lane >> 4, n16 = lane & 15;
     const int G = Hq / Hkv;
     const int total_units = header[0] * Hkv * n_row_groups;
-    char *my_lds = smem + wv * kRegion;
-
-    // LDS byte offsets of the V^T tile (unit = 16 bytes = the 8 k-slots of one channel for one lane group):
-    //   unit(d = 8c + dd, grp) = 16 * (4 dd + grp) + ((c + 2 dd) & 15)
-    // writer lane = (tq = g, c = n16) for dd = 0..7; reader lane = (g, m = n16) for channel 16 dt + m.
-    uint32_t wr_off[8], rd_off[8];
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) wr_off[dd] = 16u * (16u * (4u * dd + g) + ((n16 + 2u * dd) & 15u));
-    {
-        const uint32_t h = n16 >> 3, ddp = n16 & 7;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            rd_off[dt] = 16u * (16u * (4u * ddp + g) + ((2u * dt + h + 2u * ddp) & 15u));
-    }
+    char *my_lds = smem + wv * kVtBytes;
+    char *vt_wr = my_lds + 16 * (16 * g + n16);
+    const char *vt_rd = my_lds + 16 * (66 * (n16 & 7) + 16 * g + (n16 >> 3));
 
     for (;;) {
         __syncthreads();
         if (tid == 0) s_ticket = atomicAdd(&header[1], 1);
         __syncthreads();
-        const int ticket = s_ticket;
+        const int ticket = __builtin_amdgcn_readfirstlane(s_ticket);
         if (ticket >= total_units) break;
         const int rg = ticket % n_row_groups;
         const int gkv = (ticket / n_row_groups) % Hkv;
@@ -128,19 +135,23 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
         const int64_t head_bytes = (int64_t)16 * kD * 2;               // one (page, head) block
         const int first_masked = L - n + 1;                            // tokens >= this are hidden from some row
 
-        // ---- Q^T operands and per-row visibility limits ---------------------------------
-        uint4 qop[RT][4];
+        // ---- Q^T operands into LDS (shared by the four wavefronts) ------------------------
+#pragma unroll
+        for (int k = 0; k < RT; ++k) {
+            const int idx = tid + 256 * k;                             // (nt, s, lane) = (k, tid/64, tid%64)
+            const int row = r0 + 16 * k + n16;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (row < rows)
+                v = ld16(q + (((qrow0 + row / G) * Hq + gkv * G + row % G) * kD) * 2 + 64 * (tid >> 6) + 16 * g);
+            q_lds[idx] = v;
+        }
         int pos[RT];
 #pragma unroll
         for (int nt = 0; nt < RT; ++nt) {
             const int row = r0 + 16 * nt + n16;
-            const bool ok = row < rows;
-            pos[nt] = ok ? (L - n + row / G) : -1;
-            const char *qp = q + (((qrow0 + (ok ? row / G : 0)) * Hq + gkv * G + (ok ? row % G : 0)) * kD) * 2 +
-                             16 * g;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) qop[nt][s] = ok ? ld16(qp + 64 * s) : make_uint4(0, 0, 0, 0);
+            pos[nt] = row < rows ? (L - n + row / G) : -1;
         }
+        __syncthreads();
 
         float m[RT], lsum[RT];
         f32x4 o[RT][8];
@@ -157,53 +168,56 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
         const uint32_t k_lane_off = n16 * (kD * 2) + 16 * g;
         const uint32_t v_lane_off = (4 * g) * (kD * 2) + 16 * n16;
 
-        auto load_block = [&](int bi, bool want_k, bool want_v) {
+        // Page ids are wave-uniform (scalar loads: they never wait on the vector-memory counter).
+        // Loads are issued unconditionally so that the counter waits stay exact: a block's second
+        // page may lie past the split's end, then the first page is fetched again and the tail
+        // code below blanks what must not be used.
+        auto page_bases = [&](int bi, int64_t &b0, int64_t &b1) {
             const int tb = t0 + bi * kBlk;
+            const int64_t p0 = bt[tb >> 4];
+            const int64_t p1 = (tb + 16 < t1) ? bt[(tb >> 4) + 1] : p0;
+            b0 = (p0 * Hkv + gkv) * head_bytes;
+            b1 = (p1 * Hkv + gkv) * head_bytes;
+        };
+        auto load_k = [&](int64_t b0, int64_t b1) {
+            const char *kp0 = k_pages + b0 + k_lane_off, *kp1 = k_pages + b1 + k_lane_off;
 #pragma unroll
-            for (int pg = 0; pg < 2; ++pg) {
-                const bool have = tb + 16 * pg < t1;                   // wave-uniform
-                if (have) {
-                    const int64_t page = bt[(tb >> 4) + pg];
-                    const int64_t base = (page * Hkv + gkv) * head_bytes;
-                    if (want_k) {
-                        const char *kp = k_pages + base + k_lane_off;
+            for (int s = 0; s < 4; ++s) kreg[0][s] = ld16_stream(kp0 + 64 * s);
 #pragma unroll
-                        for (int s = 0; s < 4; ++s) kreg[pg][s] = ld16(kp + 64 * s);
-                    }
-                    if (want_v) {
-                        const char *vp = v_pages + base + v_lane_off;
+            for (int s = 0; s < 4; ++s) kreg[1][s] = ld16_stream(kp1 + 64 * s);
+        };
+        auto load_v = [&](int64_t b0, int64_t b1) {
+            const char *vp0 = v_pages + b0 + v_lane_off, *vp1 = v_pages + b1 + v_lane_off;
 #pragma unroll
-                        for (int ii = 0; ii < 4; ++ii) vreg[pg][ii] = ld16(vp + ii * (kD * 2));
-                    }
-                } else {
+            for (int ii = 0; ii < 4; ++ii) vreg[0][ii] = ld16_stream(vp0 + ii * (kD * 2));
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        if (want_k) kreg[pg][s] = make_uint4(0, 0, 0, 0);
-                        if (want_v) vreg[pg][s] = make_uint4(0, 0, 0, 0);
-                    }
-                }
-            }
+            for (int ii = 0; ii < 4; ++ii) vreg[1][ii] = ld16_stream(vp1 + ii * (kD * 2));
         };
 
-        int bi = wv;
-        if (bi < nblk) load_block(bi, true, true);
-
-        for (; bi < nblk; bi += kWaves) {
+        // One 32-token block; kNext: the following block's K and V are requested while this one
+        // is being processed (K right after the first product, V right after the LDS hand-over).
+        auto block = [&](int bi, auto next_tag) {
+            constexpr bool kNext = decltype(next_tag)::value;
             const int tb = t0 + bi * kBlk;
-            const bool has_next = bi + kWaves < nblk;
+            int64_t nb0 = 0, nb1 = 0;
+            if constexpr (kNext) page_bases(bi + kWaves, nb0, nb1);
 
             // ---- S^T = K Q^T ------------------------------------------------------------
             f32x4 sacc[RT][2];
 #pragma unroll
-            for (int nt = 0; nt < RT; ++nt)
+            for (int nt = 0; nt < RT; ++nt) {
+                uint4 qop[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) qop[s] = q_lds[(nt * 4 + s) * 64 + lane];
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) {
                     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) acc = Mma<T>::run(kreg[mt][s], qop[nt][s], acc);
+                    for (int s = 0; s < 4; ++s) acc = Mma<T>::run(kreg[mt][s], qop[s], acc);
                     sacc[nt][mt] = acc;
                 }
-            if (has_next) load_block(bi + kWaves, true, false);
+            }
+            if constexpr (kNext) load_k(nb0, nb1);
 
             // ---- online softmax (per lane: row n16 of each row tile, 8 of the 32 tokens) ----
             const bool need_mask = (tb + kBlk > first_masked) || (tb + kBlk > t1);
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                 }
             }
 
-            // ---- V^T tile: sanitise the tail, transpose 4x8 in registers, write to LDS ----
+            // ---- V^T tile: blank the tail, transpose 4x8 in registers, write to LDS --------
             if (tb + kBlk > L) {                       // the request's last, partial block
 #pragma unroll
                 for (int pg = 0; pg < 2; ++pg)
@@ -276,21 +290,34 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                                        __builtin_amdgcn_perm(a3, a2, 0x07060302u),
                                        __builtin_amdgcn_perm(b1, b0, 0x07060302u),
                                        __builtin_amdgcn_perm(b3, b2, 0x07060302u));
-                *reinterpret_cast<uint4 *>(my_lds + wr_off[2 * w]) = even;
-                *reinterpret_cast<uint4 *>(my_lds + wr_off[2 * w + 1]) = odd;
+                *reinterpret_cast<uint4 *>(vt_wr + 66 * 16 * (2 * w)) = even;
+                *reinterpret_cast<uint4 *>(vt_wr + 66 * 16 * (2 * w + 1)) = odd;
             }
-            if (has_next) load_block(bi + kWaves, false, true);
+            if constexpr (kNext) load_v(nb0, nb1);
 
             // ---- O^T += V^T P^T -------------------------------------------------------------
+            uint4 vt = *reinterpret_cast<const uint4 *>(vt_rd);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                const uint4 vt = *reinterpret_cast<const uint4 *>(my_lds + rd_off[dt]);
+                uint4 vt_next = vt;
+                if (dt < 7) vt_next = *reinterpret_cast<const uint4 *>(vt_rd + 32 * (dt + 1));
 #pragma unroll
                 for (int nt = 0; nt < RT; ++nt) {
                     o[nt][dt] = Mma<T>::run(vt, pop[nt], o[nt][dt]);
                     if constexpr (Mma<T>::kSplitP) o[nt][dt] = Mma<T>::run(vt, pop_lo[nt], o[nt][dt]);
                 }
+                vt = vt_next;
             }
+        };
+
+        int bi = wv;
+        if (bi < nblk) {
+            int64_t b0, b1;
+            page_bases(bi, b0, b1);
+            load_k(b0, b1);
+            load_v(b0, b1);
+            for (; bi + kWaves < nblk; bi += kWaves) block(bi, std::true_type{});
+            block(bi, std::false_type{});
         }
 
         // ---- merge the four wavefronts' states through LDS --------------------------------
