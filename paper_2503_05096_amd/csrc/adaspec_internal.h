@@ -25,6 +25,8 @@ struct AttnPlan {
     size_t off_row_req;     // int32[TQ]
     size_t off_split_base;  // int32[B + 1]: first item of each request
     size_t off_item_req;    // int32[max_items]
+    size_t off_item_order;  // int32[max_items]: items sorted by decreasing length (schedule order)
+    size_t off_unit_meta;   // int32[max_items][8] in schedule order: request, split, n_splits, L, n, cu_q, item, 0
     size_t off_part_ml;     // float[max_items][Hkv][max_rows][2]  (m in log2 units, l)
     size_t off_part_o;      // float[max_items][Hkv][max_rows][d]
     size_t total_bytes;

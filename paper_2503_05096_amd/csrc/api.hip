@@ -51,7 +51,7 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
     const int64_t pairs = (int64_t)d.batch * d.n_kv_heads;
     if (fast_path) {
         p.block_tokens = 32;
-        p.split_tokens = pairs >= 512 ? 1024 : (pairs >= 128 ? 512 : 256);
+        p.split_tokens = pairs >= 512 ? 4096 : (pairs >= 256 ? 2048 : (pairs >= 128 ? 1024 : (pairs >= 32 ? 512 : 256)));
     } else {
         p.block_tokens = 64;
         p.split_tokens = 256;
@@ -66,6 +66,8 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
     p.off_row_req = off;    off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 4, 256);
     p.off_split_base = off; off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
     p.off_item_req = off;   off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
+    p.off_item_order = off; off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
+    p.off_unit_meta = off;  off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 32, 256);
     p.off_part_ml = off;
     off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * 2 * sizeof(float), 256);
     p.off_part_o = off;

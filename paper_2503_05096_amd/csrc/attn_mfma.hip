@@ -86,13 +86,17 @@ __device__ __forceinline__ uint4 ld16_stream(const char *p)
 constexpr int kVtUnits = 66 * 7 + 64;
 constexpr int kVtBytes = ((kVtUnits * 16 + 255) / 256) * 256;
 
+// Everything a workgroup needs to know about one work unit; all wave-uniform.
+struct Unit {
+    int item, gkv, i, ns, L, n, rows, r0, t0, t1, nblk;
+    int64_t qrow0, bt_off;      // first query row; offset of the request's row in block_table
+};
+
 template <class T, int RT>
 __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     const char *__restrict__ q, const char *__restrict__ k_pages, const char *__restrict__ v_pages,
-    const int32_t *__restrict__ block_table, const int32_t *__restrict__ ctx_lens,
-    const int32_t *__restrict__ spec_lens, void *__restrict__ out, int32_t *__restrict__ header,
-    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ split_base,
-    const int32_t *__restrict__ item_req, float *__restrict__ part_ml, float *__restrict__ part_o,
+    const int32_t *__restrict__ block_table, void *__restrict__ out, int32_t *__restrict__ header,
+    const int32_t *__restrict__ unit_meta, float *__restrict__ part_ml, float *__restrict__ part_o,
     int Hq, int Hkv, int max_pages_per_req, int max_rows, int n_row_groups, float scale_log2,
     int out_dtype)
 {
@@ -102,54 +106,113 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     __shared__ __attribute__((aligned(16))) char smem[kSmem];
     __shared__ __attribute__((aligned(16))) uint4 q_lds[RT * 4 * 64];   // Q^T operands, MFMA lane order
     __shared__ float s_m[kWaves][kRows], s_l[kWaves][kRows], s_mstar[kRows];
-    __shared__ int s_ticket;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave-uniform by construction
     const int g = lane >> 4, n16 = lane & 15;
     const int G = Hq / Hkv;
     const int total_units = header[0] * Hkv * n_row_groups;
+    const int64_t head_bytes = (int64_t)16 * kD * 2;                // one (page, head) block
     char *my_lds = smem + wv * kVtBytes;
     char *vt_wr = my_lds + 16 * (16 * g + n16);
     const char *vt_rd = my_lds + 16 * (66 * (n16 & 7) + 16 * g + (n16 >> 3));
+    float *obuf = reinterpret_cast<float *>(smem);
 
-    for (;;) {
-        __syncthreads();
-        if (tid == 0) s_ticket = atomicAdd(&header[1], 1);
-        __syncthreads();
-        const int ticket = __builtin_amdgcn_readfirstlane(s_ticket);
-        if (ticket >= total_units) break;
-        const int rg = ticket % n_row_groups;
-        const int gkv = (ticket / n_row_groups) % Hkv;
-        const int item = ticket / (n_row_groups * Hkv);
-        const int i = item_req[item];
-        const int s0 = split_base[i], ns = split_base[i + 1] - s0, sp = item - s0;
-        const int L = ctx_lens[i], n = spec_lens[i] + 1;
-        const int rows = n * G, r0 = rg * kRows;
-        if (r0 >= rows) continue;
-        const int slen = split_len_of(L, ns, kBlk);
-        const int t0 = sp * slen, t1 = min(L, t0 + slen);
-        const int nblk = (t1 - t0 + kBlk - 1) / kBlk;
-        const int64_t qrow0 = cu_q[i];
-        const int32_t *bt = block_table + (int64_t)i * max_pages_per_req;
-        const int64_t head_bytes = (int64_t)16 * kD * 2;               // one (page, head) block
-        const int first_masked = L - n + 1;                            // tokens >= this are hidden from some row
+    // K operand: lane (g, m) <- token 16 mt + m, channels 32 s + 8 g .. +7
+    // V raw:     lane (tq = g, c = n16) <- token 16 pg + 4 tq + i, channels 8 c .. 8 c + 7
+    uint4 kreg[2][4], vreg[2][4];
+    const uint32_t k_lane_off = n16 * (kD * 2) + 16 * g;
+    const uint32_t v_lane_off = (4 * g) * (kD * 2) + 16 * n16;
 
-        // ---- Q^T operands into LDS (shared by the four wavefronts) ------------------------
+    // ---- work-unit bookkeeping ----------------------------------------------------------------
+    // Units are listed longest first.  Workgroup w of W takes them in "snake" order
+    // (w, 2W-1-w, 2W+w, ...): every workgroup gets a similar mix of long and short units without
+    // any atomic, and the next unit is known ahead of time so its data can be requested early.
+    const int W = gridDim.x, wg = blockIdx.x;
+    int round = 0;
+    auto next_unit = [&](Unit &u) -> bool {
+        for (; round * W < total_units; ++round) {
+            const int idx = round * W + ((round & 1) ? (W - 1 - wg) : wg);
+            if (idx >= total_units) continue;
+            const int rg = idx % n_row_groups;
+            u.gkv = (idx / n_row_groups) % Hkv;
+            const int32_t *mt = unit_meta + 8 * (int64_t)(idx / (n_row_groups * Hkv));
+            u.i = mt[0];
+            const int sp = mt[1];
+            u.ns = mt[2]; u.L = mt[3]; u.n = mt[4]; u.qrow0 = mt[5]; u.item = mt[6];
+            u.rows = u.n * G; u.r0 = rg * kRows;
+            if (u.r0 >= u.rows) continue;
+            const int slen = split_len_of(u.L, u.ns, kBlk);
+            u.t0 = sp * slen; u.t1 = min(u.L, u.t0 + slen);
+            u.nblk = (u.t1 - u.t0 + kBlk - 1) / kBlk;
+            u.bt_off = (int64_t)u.i * max_pages_per_req;
+            ++round;
+            return true;
+        }
+        return false;
+    };
+
+    // Page ids are wave-uniform (scalar loads: they never wait on the vector-memory counter).
+    // Loads are issued unconditionally so that the counter waits stay exact: a block's second
+    // page may lie past the split's end, then the first page is fetched again and the tail
+    // code below blanks what must not be used.
+    auto page_bases = [&](const Unit &u, int bi, int64_t &b0, int64_t &b1) {
+        const int tb = u.t0 + bi * kBlk;
+        const int64_t p0 = block_table[u.bt_off + (tb >> 4)];
+        const int64_t p1 = (tb + 16 < u.t1) ? block_table[u.bt_off + (tb >> 4) + 1] : p0;
+        b0 = (p0 * Hkv + u.gkv) * head_bytes;
+        b1 = (p1 * Hkv + u.gkv) * head_bytes;
+    };
+    auto load_k = [&](int64_t b0, int64_t b1) {
+        const char *kp0 = k_pages + b0 + k_lane_off, *kp1 = k_pages + b1 + k_lane_off;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kreg[0][s] = ld16_stream(kp0 + 64 * s);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kreg[1][s] = ld16_stream(kp1 + 64 * s);
+    };
+    auto load_v = [&](int64_t b0, int64_t b1) {
+        const char *vp0 = v_pages + b0 + v_lane_off, *vp1 = v_pages + b1 + v_lane_off;
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) vreg[0][ii] = ld16_stream(vp0 + ii * (kD * 2));
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) vreg[1][ii] = ld16_stream(vp1 + ii * (kD * 2));
+    };
+    // request the first block of this wavefront for unit u (if it has one)
+    auto first_loads = [&](const Unit &u) {
+        if (wv < u.nblk) {
+            int64_t b0, b1;
+            page_bases(u, wv, b0, b1);
+            load_k(b0, b1);
+            load_v(b0, b1);
+        }
+    };
+    // this thread's share of the unit's Q^T operands: entry (nt = k, s = tid / 64, lane = tid % 64)
+    auto load_q = [&](const Unit &u, uint4 (&qv)[RT]) {
 #pragma unroll
         for (int k = 0; k < RT; ++k) {
-            const int idx = tid + 256 * k;                             // (nt, s, lane) = (k, tid/64, tid%64)
-            const int row = r0 + 16 * k + n16;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row < rows)
-                v = ld16(q + (((qrow0 + row / G) * Hq + gkv * G + row % G) * kD) * 2 + 64 * (tid >> 6) + 16 * g);
-            q_lds[idx] = v;
+            const int row = u.r0 + 16 * k + n16;
+            qv[k] = make_uint4(0, 0, 0, 0);
+            if (row < u.rows)
+                qv[k] = ld16(q + (((u.qrow0 + row / G) * Hq + u.gkv * G + row % G) * kD) * 2 + 64 * wv + 16 * g);
         }
+    };
+
+    Unit cur, nxt;
+    bool have = next_unit(cur);
+    uint4 qv[RT];
+    if (have) { load_q(cur, qv); first_loads(cur); }
+
+    while (have) {
+        const Unit u = cur;
+        const bool have_next = next_unit(nxt);
+        const int first_masked = u.L - u.n + 1;                    // tokens >= this are hidden from some row
+#pragma unroll
+        for (int k = 0; k < RT; ++k) q_lds[tid + 256 * k] = qv[k];
         int pos[RT];
 #pragma unroll
         for (int nt = 0; nt < RT; ++nt) {
-            const int row = r0 + 16 * nt + n16;
-            pos[nt] = row < rows ? (L - n + row / G) : -1;
+            const int row = u.r0 + 16 * nt + n16;
+            pos[nt] = row < u.rows ? (u.L - u.n + row / G) : -1;
         }
         __syncthreads();
 
@@ -162,45 +225,13 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
             for (int dt = 0; dt < 8; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
-        // K operand: lane (g, m) <- token 16 mt + m, channels 32 s + 8 g .. +7
-        // V raw:     lane (tq = g, c = n16) <- token 16 pg + 4 tq + i, channels 8 c .. 8 c + 7
-        uint4 kreg[2][4], vreg[2][4];
-        const uint32_t k_lane_off = n16 * (kD * 2) + 16 * g;
-        const uint32_t v_lane_off = (4 * g) * (kD * 2) + 16 * n16;
-
-        // Page ids are wave-uniform (scalar loads: they never wait on the vector-memory counter).
-        // Loads are issued unconditionally so that the counter waits stay exact: a block's second
-        // page may lie past the split's end, then the first page is fetched again and the tail
-        // code below blanks what must not be used.
-        auto page_bases = [&](int bi, int64_t &b0, int64_t &b1) {
-            const int tb = t0 + bi * kBlk;
-            const int64_t p0 = bt[tb >> 4];
-            const int64_t p1 = (tb + 16 < t1) ? bt[(tb >> 4) + 1] : p0;
-            b0 = (p0 * Hkv + gkv) * head_bytes;
-            b1 = (p1 * Hkv + gkv) * head_bytes;
-        };
-        auto load_k = [&](int64_t b0, int64_t b1) {
-            const char *kp0 = k_pages + b0 + k_lane_off, *kp1 = k_pages + b1 + k_lane_off;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) kreg[0][s] = ld16_stream(kp0 + 64 * s);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) kreg[1][s] = ld16_stream(kp1 + 64 * s);
-        };
-        auto load_v = [&](int64_t b0, int64_t b1) {
-            const char *vp0 = v_pages + b0 + v_lane_off, *vp1 = v_pages + b1 + v_lane_off;
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) vreg[0][ii] = ld16_stream(vp0 + ii * (kD * 2));
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) vreg[1][ii] = ld16_stream(vp1 + ii * (kD * 2));
-        };
-
         // One 32-token block; kNext: the following block's K and V are requested while this one
         // is being processed (K right after the first product, V right after the LDS hand-over).
         auto block = [&](int bi, auto next_tag) {
             constexpr bool kNext = decltype(next_tag)::value;
-            const int tb = t0 + bi * kBlk;
+            const int tb = u.t0 + bi * kBlk;
             int64_t nb0 = 0, nb1 = 0;
-            if constexpr (kNext) page_bases(bi + kWaves, nb0, nb1);
+            if constexpr (kNext) page_bases(u, bi + kWaves, nb0, nb1);
 
             // ---- S^T = K Q^T ------------------------------------------------------------
             f32x4 sacc[RT][2];
@@ -220,7 +251,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
             if constexpr (kNext) load_k(nb0, nb1);
 
             // ---- online softmax (per lane: row n16 of each row tile, 8 of the 32 tokens) ----
-            const bool need_mask = (tb + kBlk > first_masked) || (tb + kBlk > t1);
+            const bool need_mask = (tb + kBlk > first_masked) || (tb + kBlk > u.t1);
             uint4 pop[RT], pop_lo[RT];
 #pragma unroll
             for (int nt = 0; nt < RT; ++nt) {
@@ -230,7 +261,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
 #pragma unroll
                     for (int r = 0; r < 4; ++r) sv[4 * mt + r] = sacc[nt][mt][r];
                 if (need_mask) {
-                    const int lim = min(pos[nt], t1 - 1);
+                    const int lim = min(pos[nt], u.t1 - 1);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const int t = tb + 16 * (e >> 2) + 4 * g + (e & 3);
@@ -269,12 +300,12 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
             }
 
             // ---- V^T tile: blank the tail, transpose 4x8 in registers, write to LDS --------
-            if (tb + kBlk > L) {                       // the request's last, partial block
+            if (tb + kBlk > u.L) {                     // the request's last, partial block
 #pragma unroll
                 for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
                     for (int ii = 0; ii < 4; ++ii)
-                        if (tb + 16 * pg + 4 * g + ii >= L) vreg[pg][ii] = make_uint4(0, 0, 0, 0);
+                        if (tb + 16 * pg + 4 * g + ii >= u.L) vreg[pg][ii] = make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
@@ -310,27 +341,26 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
             }
         };
 
-        int bi = wv;
-        if (bi < nblk) {
-            int64_t b0, b1;
-            page_bases(bi, b0, b1);
-            load_k(b0, b1);
-            load_v(b0, b1);
-            for (; bi + kWaves < nblk; bi += kWaves) block(bi, std::true_type{});
+        if (wv < u.nblk) {
+            int bi = wv;
+            for (; bi + kWaves < u.nblk; bi += kWaves) block(bi, std::true_type{});
             block(bi, std::false_type{});
         }
 
-        // ---- merge the four wavefronts' states through LDS --------------------------------
-        // m* = max over wavefronts, each state rescaled by 2^(m - m*); the O tiles are summed
-        // into one [rows][d] fp32 buffer (aliasing the V^T tiles) one wavefront after another.
+        // ---- next unit: request its first K/V block and its Q rows now, so that they travel while
+        // this unit's states are merged and written out.
 #pragma unroll
         for (int nt = 0; nt < RT; ++nt) {
             lsum[nt] += __shfl_xor(lsum[nt], 16, kWave);
             lsum[nt] += __shfl_xor(lsum[nt], 32, kWave);
             if (g == 0) s_m[wv][16 * nt + n16] = m[nt];
         }
-        __syncthreads();                                   // also: every wave is done with its V^T tile
-        float *obuf = reinterpret_cast<float *>(smem);
+        if (have_next) { load_q(nxt, qv); first_loads(nxt); }
+        __syncthreads();            // s_m complete; every wavefront is done with its V^T tile and q_lds
+
+        // ---- merge the four wavefronts' states through LDS --------------------------------
+        // m* = max over wavefronts, each state rescaled by 2^(m - m*); the O tiles are summed
+        // into one [rows][d] fp32 buffer (aliasing the V^T tiles) one wavefront after another.
         float fsc[RT];
 #pragma unroll
         for (int nt = 0; nt < RT; ++nt) {
@@ -365,13 +395,13 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
         for (int it = 0; it < 2 * RT; ++it) {
             const int idx = tid + 256 * it;
             const int rl = idx >> 5, c4 = idx & 31;
-            const int row = r0 + rl;
-            if (row >= rows) continue;
+            const int row = u.r0 + rl;
+            if (row >= u.rows) continue;
             const f32x4 acc = *reinterpret_cast<const f32x4 *>(obuf + rl * kORowStride + 4 * c4);
             const float ltot = (s_l[0][rl] + s_l[1][rl]) + (s_l[2][rl] + s_l[3][rl]);
-            if (ns == 1) {
+            if (u.ns == 1) {
                 const float inv = 1.0f / ltot;
-                const int64_t obase = ((qrow0 + row / G) * Hq + gkv * G + row % G) * (int64_t)kD + 4 * c4;
+                const int64_t obase = ((u.qrow0 + row / G) * Hq + u.gkv * G + row % G) * (int64_t)kD + 4 * c4;
                 if (out_dtype == ADASPEC_F32) {
                     *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + obase) = acc * inv;
                 } else {
@@ -380,7 +410,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                     *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + obase) = pk;
                 }
             } else {
-                const int64_t idx_row = ((int64_t)item * Hkv + gkv) * max_rows + row;
+                const int64_t idx_row = ((int64_t)u.item * Hkv + u.gkv) * max_rows + row;
                 *reinterpret_cast<f32x4 *>(part_o + idx_row * kD + 4 * c4) = acc;
                 if (c4 == 0) {
                     part_ml[idx_row * 2] = s_mstar[rl];
@@ -388,6 +418,10 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                 }
             }
         }
+        // the next loop iteration overwrites q_lds and the V^T tiles: everyone must be done reading obuf
+        __syncthreads();
+        cur = nxt;
+        have = have_next;
     }
 }
 
@@ -405,15 +439,24 @@ hipError_t launch_attn_mfma(const AttnArgs &a)
     const int n_row_groups = ceil_div(p.max_rows, 16 * rt);
     const int64_t max_units = (int64_t)p.max_items * d.n_kv_heads * n_row_groups;
     if (max_units == 0) return hipSuccess;
-    const int grid = (int)(max_units < 2048 ? max_units : 2048);
     auto launch = [&](auto tag, auto rt_tag) {
         using T = decltype(tag);
         constexpr int RT = decltype(rt_tag)::value;
+        // one resident "slot" per workgroup: the static snake schedule balances over exactly these
+        static int slots = 0;
+        if (slots == 0) {
+            int dev = 0, cus = 256, per_cu = 1;
+            if (hipGetDevice(&dev) == hipSuccess) {
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0);
+            }
+            slots = cus * (per_cu > 0 ? per_cu : 1);
+        }
+        const int grid = (int)(max_units < slots ? max_units : slots);
         hipLaunchKernelGGL((attn_mfma_kernel<T, RT>), dim3(grid), dim3(256), 0, a.stream,
                            (const char *)a.q, (const char *)a.k_pages, (const char *)a.v_pages,
-                           a.block_table, a.ctx_lens, a.spec_lens, a.out, (int32_t *)(a.ws + p.off_header),
-                           (const int32_t *)(a.ws + p.off_cu_q), (const int32_t *)(a.ws + p.off_split_base),
-                           (const int32_t *)(a.ws + p.off_item_req), (float *)(a.ws + p.off_part_ml),
+                           a.block_table, a.out, (int32_t *)(a.ws + p.off_header),
+                           (const int32_t *)(a.ws + p.off_unit_meta), (float *)(a.ws + p.off_part_ml),
                            (float *)(a.ws + p.off_part_o), d.n_q_heads, d.n_kv_heads, d.max_pages_per_req,
                            p.max_rows, n_row_groups, a.scale_log2, d.out_dtype);
     };

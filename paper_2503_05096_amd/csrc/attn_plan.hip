@@ -14,12 +14,13 @@ constexpr int kPlanThreads = 1024;
 // write outside its workspace.
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
     const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ spec_lens, int B, int total_q,
-    int max_spec_len, int split_tokens, int max_items, int32_t *__restrict__ header,
+    int max_spec_len, int split_tokens, int block_tokens, int max_items, int32_t *__restrict__ header,
     int32_t *__restrict__ cu_q, int32_t *__restrict__ row_req, int32_t *__restrict__ split_base,
-    int32_t *__restrict__ item_req)
+    int32_t *__restrict__ item_req, int32_t *__restrict__ item_order, int32_t *__restrict__ unit_meta)
 {
     __shared__ int tot_n[kPlanThreads / kWave], tot_s[kPlanThreads / kWave];
     __shared__ int carry[2];
+    __shared__ int hist[64];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (tid == 0) { carry[0] = 0; carry[1] = 0; }
     __syncthreads();
@@ -55,6 +56,37 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
         header[0] = min(carry[1], max_items);   // number of work items
         header[1] = 0;                          // ticket counter of the main kernel
     }
+    // Schedule order: longest items first (counting sort on the length in token blocks), so that
+    // the workgroups that pull tickets last get the short items and the tail of the launch is short.
+    const int n_items = min(carry[1], max_items);
+    const int nbins = min(64, max(1, split_tokens / block_tokens));
+    if (tid < 64) hist[tid] = 0;
+    __syncthreads();
+    auto bin_of = [&](int item) {
+        const int i = item_req[item];
+        const int L = max(ctx_lens[i], 1);
+        const int ns = ceil_div(L, split_tokens), s = item - split_base[i];
+        const int slen = split_len_of(L, ns, block_tokens);
+        const int len = min(L, (s + 1) * slen) - s * slen;
+        const int scaled = (int)(((int64_t)max(len, 1) * nbins + split_tokens - 1) / split_tokens);
+        return nbins - min(max(scaled, 1), nbins);   // bin 0 = longest
+    };
+    for (int item = tid; item < n_items; item += kPlanThreads) atomicAdd(&hist[bin_of(item)], 1);
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int b = 0; b < nbins; ++b) { const int c = hist[b]; hist[b] = run; run += c; }
+    }
+    __syncthreads();
+    for (int item = tid; item < n_items; item += kPlanThreads) {
+        const int pos = atomicAdd(&hist[bin_of(item)], 1);
+        item_order[pos] = item;
+        const int i = item_req[item];
+        const int L = max(ctx_lens[i], 1);
+        int32_t *m = unit_meta + 8 * (int64_t)pos;
+        m[0] = i; m[1] = item - split_base[i]; m[2] = ceil_div(L, split_tokens); m[3] = L;
+        m[4] = min(max(spec_lens[i], 0), max_spec_len) + 1; m[5] = cu_q[i]; m[6] = item; m[7] = 0;
+    }
 }
 
 hipError_t launch_attn_plan(const AttnArgs &a)
@@ -62,9 +94,10 @@ hipError_t launch_attn_plan(const AttnArgs &a)
     const AttnPlan &p = a.plan;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, a.stream, a.ctx_lens,
                        a.spec_lens, a.dims.batch, a.dims.total_q, a.dims.max_spec_len, p.split_tokens,
-                       p.max_items, (int32_t *)(a.ws + p.off_header), (int32_t *)(a.ws + p.off_cu_q),
-                       (int32_t *)(a.ws + p.off_row_req), (int32_t *)(a.ws + p.off_split_base),
-                       (int32_t *)(a.ws + p.off_item_req));
+                       p.block_tokens, p.max_items, (int32_t *)(a.ws + p.off_header),
+                       (int32_t *)(a.ws + p.off_cu_q), (int32_t *)(a.ws + p.off_row_req),
+                       (int32_t *)(a.ws + p.off_split_base), (int32_t *)(a.ws + p.off_item_req),
+                       (int32_t *)(a.ws + p.off_item_order), (int32_t *)(a.ws + p.off_unit_meta));
     return hipGetLastError();
 }
 

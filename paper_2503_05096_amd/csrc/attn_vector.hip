@@ -22,7 +22,8 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ ctx_lens,
     const int32_t *__restrict__ spec_lens, void *__restrict__ out, int32_t *__restrict__ header,
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ split_base,
-    const int32_t *__restrict__ item_req, float *__restrict__ part_ml, float *__restrict__ part_o,
+    const int32_t *__restrict__ item_req, const int32_t *__restrict__ item_order,
+    float *__restrict__ part_ml, float *__restrict__ part_o,
     int Hq, int Hkv, int d, int P, int max_pages_per_req, int max_rows, int n_row_chunks,
     int split_tokens, int block_tokens, float scale_log2, int out_dtype)
 {
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
         if (ticket >= total_units) break;
         const int rc = ticket % n_row_chunks;
         const int g = (ticket / n_row_chunks) % Hkv;
-        const int item = ticket / (n_row_chunks * Hkv);
+        const int item = item_order[ticket / (n_row_chunks * Hkv)];
         const int i = item_req[item];
         const int s0 = split_base[i], ns = split_base[i + 1] - s0, s = item - s0;
         const int L = ctx_lens[i], n = spec_lens[i] + 1;
@@ -168,7 +169,8 @@ hipError_t launch_attn_vector(const AttnArgs &a)
                            a.v_pages, a.block_table, a.ctx_lens, a.spec_lens, a.out,
                            (int32_t *)(a.ws + p.off_header), (const int32_t *)(a.ws + p.off_cu_q),
                            (const int32_t *)(a.ws + p.off_split_base),
-                           (const int32_t *)(a.ws + p.off_item_req), (float *)(a.ws + p.off_part_ml),
+                           (const int32_t *)(a.ws + p.off_item_req),
+                           (const int32_t *)(a.ws + p.off_item_order), (float *)(a.ws + p.off_part_ml),
                            (float *)(a.ws + p.off_part_o), d.n_q_heads, d.n_kv_heads, d.head_dim,
                            d.page_size, d.max_pages_per_req, p.max_rows, n_row_chunks, p.split_tokens,
                            p.block_tokens, a.scale_log2, d.out_dtype);
