@@ -51,7 +51,7 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
     const int64_t pairs = (int64_t)d.batch * d.n_kv_heads;
     if (fast_path) {
         p.block_tokens = 32;
-        p.split_tokens = pairs >= 512 ? 4096 : (pairs >= 256 ? 2048 : (pairs >= 128 ? 1024 : (pairs >= 32 ? 512 : 256)));
+        p.split_tokens = pairs >= 512 ? 2048 : (pairs >= 256 ? 2048 : (pairs >= 128 ? 1024 : (pairs >= 32 ? 512 : 256)));
     } else {
         p.block_tokens = 64;
         p.split_tokens = 256;
