@@ -43,8 +43,21 @@ __device__ __forceinline__ void keep_packed(uint4 &v)
     asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
 }
 
+typedef short short2v __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// sum over the 16 lanes of a DPP row (every lane of the row ends up with the row's total)
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));  // row_ror 4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));  // row_ror 8
+    return v;
+}
+
 struct FastScratch {
-    double sw[kFW][16];      // per-wavefront totals of every step
+    float  sw[kFW][16][4];   // per step: the four 16-lane row sums of every wavefront
     double st[16];           // block totals of every step
     float  wm[kFW], wz[kFW];
     float  av[kFW];
@@ -78,24 +91,24 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     const uint32_t tid16 = (uint32_t)tid * 16u;
 
     // ---- 1. the logits row, once ---------------------------------------------------------
-    // Loads are unconditional (the lane offset is clamped into the row) so that all of them are
-    // in flight together; chunks past the end of the row are blanked afterwards, which only the
-    // last step(s) need (wave-uniform test).
-    const uint32_t last16 = (uint32_t)(nchunks - 1) * 16u;
-    auto chunk_ptr = [&](const char *row, int it) {
-        const uint32_t base = min((uint32_t)it * (kFT * 16u), last16);      // wave-uniform
-        return row + base + min(tid16, last16 - base);
+    // Buffer loads: the row's base and size sit in a scalar descriptor, the lane supplies a 32-bit
+    // offset (no 64-bit address registers), and chunks past the end of the row read as zero.  All
+    // loads of the row are in flight together.
+    const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(lrow), 0, V * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, V * 2, 0x00020000);
+    auto load_chunk = [&](const __amdgpu_buffer_rsrc_t &rs, int it) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)tid16, it * (kFT * 16), 0);
+        return make_uint4(v.x, v.y, v.z, v.w);
     };
     uint4 lg[ITER];
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) lg[it] = *reinterpret_cast<const uint4 *>(chunk_ptr(lrow, it));
+    for (int it = 0; it < ITER; ++it) lg[it] = load_chunk(rl, it);
     const bool sampled = T != 0.0f;
     const bool has_q = sampled && !bonus;
     uint4 qb[kQPre];
     if (has_q) {
 #pragma unroll
-        for (int it = 0; it < kQPre && it < ITER; ++it)
-            qb[it] = *reinterpret_cast<const uint4 *>(chunk_ptr(prow, it));
+        for (int it = 0; it < kQPre && it < ITER; ++it) qb[it] = load_chunk(rq, it);
     }
 #pragma unroll
     for (int it = 0; it < ITER; ++it)
@@ -132,16 +145,46 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     }
 
     // ---- 2. maximum and normaliser ---------------------------------------------------------
+    // Both 16-bit formats are sign-magnitude, so a packed SIGNED 16-bit integer maximum started at
+    // +0 yields max(0, largest positive logit) with one instruction per two elements.  A row
+    // without any positive logit (block result 0) takes the exact float maximum instead.
     const float c = 1.4426950408889634f / T;
-    float mt = -1.0e30f;
+    short2v pm = {0, 0};
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        keep_packed(lg[it]);
         const uint32_t *w = &lg[it].x;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) mt = fmaxf(mt, fmaxf(P::lo(w[e]), P::hi(w[e])));
-        __builtin_amdgcn_sched_barrier(0);
+        for (int e = 0; e < 4; ++e) pm = __builtin_elementwise_max(pm, __builtin_bit_cast(short2v, w[e]));
     }
+    {
+        const int mw = wave_max(max((int)pm.x, (int)pm.y));
+        if (lane == 0) sm.ai[wv] = mw;
+        if (tid == 0) { sm.first_hit = kFT; sm.last_pos = -1; }
+    }
+    __syncthreads();
+    int mbits = sm.ai[0];
+#pragma unroll
+    for (int w = 1; w < kFW; ++w) mbits = max(mbits, sm.ai[w]);
+    float m = P::lo((uint32_t)mbits);
+    if (mbits == 0) {                         // rare: no positive logit in the row
+        float mt = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            keep_packed(lg[it]);
+            const uint32_t *w = &lg[it].x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mt = fmaxf(mt, fmaxf(P::lo(w[e]), P::hi(w[e])));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mt = wave_max(mt);
+        if (lane == 0) sm.wm[wv] = mt;
+        __syncthreads();
+        m = sm.wm[0];
+#pragma unroll
+        for (int w = 1; w < kFW; ++w) m = fmaxf(m, sm.wm[w]);
+    }
+    // e_v = 2^(l_v * c - m * c): the same fused expression everywhere, so Z and every p_v agree
+    const float mc = m * c;
     float zt = 0.f;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
@@ -149,25 +192,18 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         const uint32_t *w = &lg[it].x;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            zt += __builtin_amdgcn_exp2f((P::lo(w[e]) - mt) * c);
-            zt += __builtin_amdgcn_exp2f((P::hi(w[e]) - mt) * c);
+            zt += __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mc));
+            zt += __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mc));
             if (e == 1) __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    {
-        const float mw = wave_max(mt);
-        const float zw = wave_sum(zt * __builtin_amdgcn_exp2f((mt - mw) * c));
-        if (lane == 0) { sm.wm[wv] = mw; sm.wz[wv] = zw; }
-        if (tid == 0) { sm.first_hit = kFT; sm.last_pos = -1; }
-    }
+    zt = wave_sum(zt);
+    if (lane == 0) sm.wz[wv] = zt;
     __syncthreads();
-    float m = sm.wm[0];
-#pragma unroll
-    for (int w = 1; w < kFW; ++w) m = fmaxf(m, sm.wm[w]);
     double Zd = 0.0;
 #pragma unroll
-    for (int w = 0; w < kFW; ++w) Zd += (double)(sm.wz[w] * __builtin_amdgcn_exp2f((sm.wm[w] - m) * c));
+    for (int w = 0; w < kFW; ++w) Zd += (double)sm.wz[w];
     const float invZ = (float)(1.0 / Zd);
 
     if (tid == 0) {
@@ -176,7 +212,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             const uint16_t lb = *reinterpret_cast<const uint16_t *>(lrow + (int64_t)x * 2);
             const uint16_t qx16 = *reinterpret_cast<const uint16_t *>(prow + (int64_t)x * 2);
             const float lx = P::lo(lb), qx = P::lo(qx16);
-            const float px = __builtin_amdgcn_exp2f((lx - m) * c) * invZ;
+            const float px = __builtin_amdgcn_exp2f(fmaf(lx, c, -mc)) * invZ;
             flag = (qx > 0.f) ? (uniforms[2 * (int64_t)r] < px / qx) : 1;
         }
         row_flag[r] = flag;
@@ -190,30 +226,30 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             uint4 qv = make_uint4(0, 0, 0, 0);
             if (use_q) {
                 qv = qb[it % kQPre];
-                if (it + kQPre < ITER)
-                    qb[it % kQPre] = *reinterpret_cast<const uint4 *>(chunk_ptr(prow, it + kQPre));
-                if ((it + 1) * kFT > nchunks && it * kFT + tid >= nchunks) qv = make_uint4(0, 0, 0, 0);
+                if (it + kQPre < ITER) qb[it % kQPre] = load_chunk(rq, it + kQPre);
             }
             keep_packed(lg[it]);
             const uint32_t *w = &lg[it].x, *qw = &qv.x;
             float acc = 0.f;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float ea = __builtin_amdgcn_exp2f((P::lo(w[e]) - m) * c);
-                const float eb = __builtin_amdgcn_exp2f((P::hi(w[e]) - m) * c);
+                const float ea = __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mc));
+                const float eb = __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mc));
                 acc += fmaxf(0.f, fmaf(ea, invZ, -P::lo(qw[e])));
                 acc += fmaxf(0.f, fmaf(eb, invZ, -P::hi(qw[e])));
                 if (e == 1) __builtin_amdgcn_sched_barrier(0);
             }
-            const double t = wave_sum((double)acc);
-            if (lane == 0) sm.sw[wv][it] = t;
+            acc = row16_sum(acc);             // fp32 over 16 lanes; the 64 row sums per step are added in fp64
+            if ((lane & 15) == 0) sm.sw[wv][it][lane >> 4] = acc;
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         if (tid < ITER) {
             double t = 0.0;
 #pragma unroll 1
-            for (int w = 0; w < kFW; ++w) t = t + sm.sw[w][tid];
+            for (int w = 0; w < kFW; ++w)
+                t = t + (((double)sm.sw[w][tid][0] + (double)sm.sw[w][tid][1]) +
+                         ((double)sm.sw[w][tid][2] + (double)sm.sw[w][tid][3]));
             sm.st[tid] = t;
         }
         __syncthreads();
@@ -255,14 +291,14 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         if (it == itstar) lstar = lg[it];
     const int cstar = itstar * kFT + tid;
     uint4 qstar = make_uint4(0, 0, 0, 0);
-    if (use_q && cstar < nchunks) qstar = *reinterpret_cast<const uint4 *>(chunk_ptr(prow, itstar));
+    if (use_q) qstar = load_chunk(rq, itstar);
     float rv[8], sstar = 0.f;
     {
         const uint32_t *w = &lstar.x, *qw = &qstar.x;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {          // same expressions, same order as in the streaming pass
-            const float ea = __builtin_amdgcn_exp2f((P::lo(w[e]) - m) * c);
-            const float eb = __builtin_amdgcn_exp2f((P::hi(w[e]) - m) * c);
+            const float ea = __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mc));
+            const float eb = __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mc));
             rv[2 * e] = fmaxf(0.f, fmaf(ea, invZ, -P::lo(qw[e])));
             rv[2 * e + 1] = fmaxf(0.f, fmaf(eb, invZ, -P::hi(qw[e])));
             sstar += rv[2 * e];
@@ -271,7 +307,9 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     }
     double base = before;
 #pragma unroll 1
-    for (int w = 0; w < wv; ++w) base = base + sm.sw[w][itstar];
+    for (int w = 0; w < wv; ++w)
+        base = base + (((double)sm.sw[w][itstar][0] + (double)sm.sw[w][itstar][1]) +
+                       ((double)sm.sw[w][itstar][2] + (double)sm.sw[w][itstar][3]));
     const double wi = wave_scan_incl((double)sstar, lane);
     double we = __shfl_up(wi, 1, kWave);
     if (lane == 0) we = 0.0;
