@@ -70,24 +70,21 @@ struct FastScratch {
 template <class DT, int ITER>
 __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
-    const int32_t *__restrict__ draft_tokens, const float *__restrict__ uniforms,
-    const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature,
-    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ row_req, int V, int max_spec_len,
+    const float *__restrict__ uniforms, const int32_t *__restrict__ row_meta, int V,
     int64_t lstride, int64_t pstride, int32_t *__restrict__ row_flag, int32_t *__restrict__ row_cand)
 {
     using P = Pair16<DT>;
     __shared__ FastScratch sm;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = blockIdx.x;
-    const int i = row_req[r];
-    const int j = r - cu_q[i];
-    const int k = min(max(spec_lens[i], 0), max_spec_len);
+    // per-row record written by the plan kernel: request, position j, k, draft token, temperature, draft row
+    const int32_t *mt = row_meta + 8 * (int64_t)r;
+    const int j = mt[1], k = mt[2], x = mt[3];
+    const float T = __int_as_float(mt[4]);
     const bool bonus = j >= k;
-    const float T = temperature[i];
     const int nchunks = V >> 3;
     const char *lrow = logits + (int64_t)r * lstride * 2;
-    const char *prow = probs + (int64_t)(r - i) * pstride * 2;
-    const int x = bonus ? -1 : draft_tokens[r - i];
+    const char *prow = probs + (int64_t)mt[5] * pstride * 2;
     const uint32_t tid16 = (uint32_t)tid * 16u;
 
     // ---- 1. the logits row, once ---------------------------------------------------------
@@ -351,9 +348,8 @@ hipError_t launch_accept_fast(const AcceptArgs &a)
         using DT = decltype(tag);
         constexpr int ITER = decltype(it_tag)::value;
         hipLaunchKernelGGL((accept_fast_kernel<DT, ITER>), dim3(d.total_q), dim3(kFT), 0, a.stream,
-                           (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.uniforms,
-                           a.spec_lens, a.temperature, (const int32_t *)(a.ws + a.plan.off_cu_q),
-                           (const int32_t *)(a.ws + a.plan.off_row_req), d.vocab, d.max_spec_len,
+                           (const char *)a.logits, (const char *)a.probs, a.uniforms,
+                           (const int32_t *)(a.ws + a.plan.off_row_meta), d.vocab,
                            d.logits_row_stride, d.probs_row_stride,
                            (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand));
     };

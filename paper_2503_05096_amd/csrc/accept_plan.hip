@@ -9,8 +9,9 @@ constexpr int kPlanThreads = 1024;
 
 // cu_q = exclusive scan of spec_lens[i] + 1, row_req = request of each logits row.
 __global__ __launch_bounds__(kPlanThreads) void accept_plan_kernel(
-    const int32_t *__restrict__ spec_lens, int B, int total_q, int max_spec_len,
-    int32_t *__restrict__ cu_q, int32_t *__restrict__ row_req)
+    const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature,
+    const int32_t *__restrict__ draft_tokens, int B, int total_q, int max_spec_len,
+    int32_t *__restrict__ cu_q, int32_t *__restrict__ row_req, int32_t *__restrict__ row_meta)
 {
     __shared__ int tot[kPlanThreads / kWave];
     __shared__ int carry;
@@ -28,8 +29,16 @@ __global__ __launch_bounds__(kPlanThreads) void accept_plan_kernel(
         const int mine = pre + inc - n;
         if (i < B) {
             cu_q[i] = mine;
-            for (int j = 0; j < n; ++j)
-                if (mine + j < total_q) row_req[mine + j] = i;
+            const int tbits = __float_as_int(temperature[i]);
+            for (int j = 0; j < n; ++j) {
+                const int r = mine + j;
+                if (r >= total_q) break;
+                row_req[r] = i;
+                int32_t *m = row_meta + 8 * (int64_t)r;
+                m[0] = i; m[1] = j; m[2] = n - 1;
+                m[3] = j < n - 1 ? draft_tokens[r - i] : -1;
+                m[4] = tbits; m[5] = j < n - 1 ? r - i : 0; m[6] = 0; m[7] = 0;
+            }
         }
         __syncthreads();
         if (tid == kPlanThreads - 1) carry = pre + inc;
@@ -41,8 +50,9 @@ __global__ __launch_bounds__(kPlanThreads) void accept_plan_kernel(
 hipError_t launch_accept_plan(const AcceptArgs &a)
 {
     hipLaunchKernelGGL(accept_plan_kernel, dim3(1), dim3(kPlanThreads), 0, a.stream, a.spec_lens,
-                       a.dims.batch, a.dims.total_q, a.dims.max_spec_len,
-                       (int32_t *)(a.ws + a.plan.off_cu_q), (int32_t *)(a.ws + a.plan.off_row_req));
+                       a.temperature, a.draft_tokens, a.dims.batch, a.dims.total_q, a.dims.max_spec_len,
+                       (int32_t *)(a.ws + a.plan.off_cu_q), (int32_t *)(a.ws + a.plan.off_row_req),
+                       (int32_t *)(a.ws + a.plan.off_row_meta));
     return hipGetLastError();
 }
 

@@ -64,6 +64,7 @@ struct AcceptPlan {
     size_t off_row_req;     // int32[TQ]
     size_t off_row_flag;    // int32[TQ]  1 = accepted (or bonus row)
     size_t off_row_cand;    // int32[TQ]  token to emit if the request stops at this row
+    size_t off_row_meta;    // int32[TQ][8]: request, position j, k, draft token, temperature bits, draft row
     size_t total_bytes;
 };
 AcceptPlan make_accept_plan(const adaspec_accept_dims &d);

@@ -99,6 +99,7 @@ AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
     p.off_row_req = off;  off = align_up(off + tq * 4, 256);
     p.off_row_flag = off; off = align_up(off + tq * 4, 256);
     p.off_row_cand = off; off = align_up(off + tq * 4, 256);
+    p.off_row_meta = off; off = align_up(off + tq * 32, 256);
     p.total_bytes = off;
     return p;
 }
