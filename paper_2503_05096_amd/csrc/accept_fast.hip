@@ -64,42 +64,75 @@ struct FastScratch {
     int    ai[kFW];
     double tau, before;
     int    itstar, retry;
+    int    row_i, row_j, row_k;
     int    first_hit, last_pos;
 };
 
 template <class DT, int ITER>
 __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
-    const float *__restrict__ uniforms, const int32_t *__restrict__ row_meta, int V,
-    int64_t lstride, int64_t pstride, int32_t *__restrict__ row_flag, int32_t *__restrict__ row_cand)
+    const int32_t *__restrict__ draft_tokens, const float *__restrict__ uniforms,
+    const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature, int B, int V,
+    int max_spec_len, int64_t lstride, int64_t pstride, int32_t *__restrict__ row_flag,
+    int32_t *__restrict__ row_cand)
 {
     using P = Pair16<DT>;
     __shared__ FastScratch sm;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = blockIdx.x;
-    // per-row record written by the plan kernel: request, position j, k, draft token, temperature, draft row
-    const int32_t *mt = row_meta + 8 * (int64_t)r;
-    const int j = mt[1], k = mt[2], x = mt[3];
-    const float T = __int_as_float(mt[4]);
-    const bool bonus = j >= k;
     const int nchunks = V >> 3;
     const char *lrow = logits + (int64_t)r * lstride * 2;
-    const char *prow = probs + (int64_t)mt[5] * pstride * 2;
     const uint32_t tid16 = (uint32_t)tid * 16u;
 
     // ---- 1. the logits row, once ---------------------------------------------------------
     // Buffer loads: the row's base and size sit in a scalar descriptor, the lane supplies a 32-bit
     // offset (no 64-bit address registers), and chunks past the end of the row read as zero.  All
-    // loads of the row are in flight together.
+    // loads of the row are in flight together; they only need the row index, so they are requested
+    // before the row's request is even known.
     const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(lrow), 0, V * 2, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, V * 2, 0x00020000);
     auto load_chunk = [&](const __amdgpu_buffer_rsrc_t &rs, int it) {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)tid16, it * (kFT * 16), 0);
         return make_uint4(v.x, v.y, v.z, v.w);
     };
+    // (the first 1024 draft lengths are requested ahead of the row: the memory counter is in order,
+    // so anything asked for after the row would only be seen once the whole row has arrived)
+    int n_first = 0;
+    if (tid < B) n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
     uint4 lg[ITER];
 #pragma unroll
     for (int it = 0; it < ITER; ++it) lg[it] = load_chunk(rl, it);
+
+    // ---- which request owns row r?  (while the loads travel)  Block scan of n_i = k_i + 1 over the
+    // requests, 1024 at a time; the thread whose request covers r publishes (i, j, k).
+    {
+        int carry = 0;
+        for (int base = 0; base < B; base += kFT) {
+            const int i = base + tid;
+            int n = n_first;
+            if (base > 0) n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+            const int inc = wave_scan_incl(n, lane);
+            if (lane == 63) sm.ai[wv] = inc;
+            __syncthreads();
+            int pre = carry, tot = carry;
+#pragma unroll
+            for (int w = 0; w < kFW; ++w) {
+                if (w < wv) pre += sm.ai[w];
+                tot += sm.ai[w];
+            }
+            const int start = pre + inc - n;
+            if (r >= start && r < start + n) { sm.row_i = i; sm.row_j = r - start; sm.row_k = n - 1; }
+            __syncthreads();
+            carry = tot;
+            if (r < carry) break;
+        }
+    }
+    const int ri = __builtin_amdgcn_readfirstlane(sm.row_i), j = __builtin_amdgcn_readfirstlane(sm.row_j),
+              k = __builtin_amdgcn_readfirstlane(sm.row_k);   // wave-uniform: the loads below are scalar
+    const bool bonus = j >= k;
+    const float T = temperature[ri];
+    const int x = bonus ? -1 : draft_tokens[r - ri];
+    const char *prow = probs + (int64_t)(r - ri) * pstride * 2;
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, V * 2, 0x00020000);
     const bool sampled = T != 0.0f;
     const bool has_q = sampled && !bonus;
     uint4 qb[kQPre];
@@ -348,8 +381,8 @@ hipError_t launch_accept_fast(const AcceptArgs &a)
         using DT = decltype(tag);
         constexpr int ITER = decltype(it_tag)::value;
         hipLaunchKernelGGL((accept_fast_kernel<DT, ITER>), dim3(d.total_q), dim3(kFT), 0, a.stream,
-                           (const char *)a.logits, (const char *)a.probs, a.uniforms,
-                           (const int32_t *)(a.ws + a.plan.off_row_meta), d.vocab,
+                           (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.uniforms,
+                           a.spec_lens, a.temperature, d.batch, d.vocab, d.max_spec_len,
                            d.logits_row_stride, d.probs_row_stride,
                            (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand));
     };

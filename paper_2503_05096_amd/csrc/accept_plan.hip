@@ -58,33 +58,51 @@ hipError_t launch_accept_plan(const AcceptArgs &a)
 
 // Sequential rule applied to the per-row results: accepted drafts up to the
 // first rejected row, then that row's candidate; if no row rejects, the bonus
-// row's candidate.  One thread per request.
-__global__ __launch_bounds__(256) void accept_emit_kernel(
-    const int32_t *__restrict__ cu_q, const int32_t *__restrict__ spec_lens,
-    const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ row_flag,
-    const int32_t *__restrict__ row_cand, int B, int max_spec_len, int out_stride,
-    int32_t *__restrict__ out_tokens, int32_t *__restrict__ out_accept_len)
+// row's candidate.  One workgroup; it scans spec_lens itself (cu_q), so it does
+// not depend on the plan kernel; one thread per request, 1024 requests at a time.
+__global__ __launch_bounds__(kPlanThreads) void accept_emit_kernel(
+    const int32_t *__restrict__ spec_lens, const int32_t *__restrict__ draft_tokens,
+    const int32_t *__restrict__ row_flag, const int32_t *__restrict__ row_cand, int B, int total_q,
+    int max_spec_len, int out_stride, int32_t *__restrict__ out_tokens,
+    int32_t *__restrict__ out_accept_len)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= B) return;
-    const int k = min(max(spec_lens[i], 0), max_spec_len);
-    const int r0 = cu_q[i], d0 = r0 - i;
-    int a = k;
-    for (int j = 0; j < k; ++j)
-        if (row_flag[r0 + j] == 0) { a = j; break; }
-    int32_t *o = out_tokens + (int64_t)i * out_stride;
-    for (int j = 0; j < a; ++j) o[j] = draft_tokens[d0 + j];
-    o[a] = row_cand[r0 + a];
-    for (int j = a + 1; j < out_stride; ++j) o[j] = -1;
-    out_accept_len[i] = a;
+    __shared__ int tot[kPlanThreads / kWave];
+    __shared__ int carry;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < B; base += kPlanThreads) {
+        const int i = base + tid;
+        const int k = i < B ? min(max(spec_lens[i], 0), max_spec_len) : -1;
+        const int n = k + 1;
+        const int inc = wave_scan_incl(n, lane);
+        if (lane == 63) tot[wv] = inc;
+        __syncthreads();
+        int pre = carry;
+        for (int w = 0; w < wv; ++w) pre += tot[w];
+        const int r0 = pre + inc - n;
+        if (i < B && r0 + n <= total_q) {
+            const int d0 = r0 - i;
+            int a = k;
+            for (int j = 0; j < k; ++j)
+                if (row_flag[r0 + j] == 0) { a = j; break; }
+            int32_t *o = out_tokens + (int64_t)i * out_stride;
+            for (int j = 0; j < a; ++j) o[j] = draft_tokens[d0 + j];
+            o[a] = row_cand[r0 + a];
+            for (int j = a + 1; j < out_stride; ++j) o[j] = -1;
+            out_accept_len[i] = a;
+        }
+        __syncthreads();
+        if (tid == kPlanThreads - 1) carry = pre + inc;
+        __syncthreads();
+    }
 }
 
 hipError_t launch_accept_emit(const AcceptArgs &a)
 {
-    hipLaunchKernelGGL(accept_emit_kernel, dim3(ceil_div(a.dims.batch, 256)), dim3(256), 0, a.stream,
-                       (const int32_t *)(a.ws + a.plan.off_cu_q), a.spec_lens, a.draft_tokens,
-                       (const int32_t *)(a.ws + a.plan.off_row_flag),
-                       (const int32_t *)(a.ws + a.plan.off_row_cand), a.dims.batch,
+    hipLaunchKernelGGL(accept_emit_kernel, dim3(1), dim3(kPlanThreads), 0, a.stream, a.spec_lens,
+                       a.draft_tokens, (const int32_t *)(a.ws + a.plan.off_row_flag),
+                       (const int32_t *)(a.ws + a.plan.off_row_cand), a.dims.batch, a.dims.total_q,
                        a.dims.max_spec_len, a.dims.out_stride, a.out_tokens, a.out_accept_len);
     return hipGetLastError();
 }

@@ -184,7 +184,8 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     a.dims = *dims; a.ws = static_cast<char *>(workspace);
     a.stream = static_cast<hipStream_t>(stream);
 
-    if (launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    // the register-resident kernel finds each row's request itself; only the vector kernel needs the plan
+    if (!fast && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     hipError_t e = fast ? launch_accept_fast(a) : launch_accept_vector(a);
