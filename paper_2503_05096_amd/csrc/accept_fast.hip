@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             if (base > 0) n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
             const int inc = wave_scan_incl(n, lane);
             if (lane == 63) sm.ai[wv] = inc;
-            __syncthreads();
+            lds_barrier();           // LDS only: the row's loads stay in flight
             int pre = carry, tot = carry;
 #pragma unroll
             for (int w = 0; w < kFW; ++w) {
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             }
             const int start = pre + inc - n;
             if (r >= start && r < start + n) { sm.row_i = i; sm.row_j = r - start; sm.row_k = n - 1; }
-            __syncthreads();
+            lds_barrier();           // LDS only: the row's loads stay in flight
             carry = tot;
             if (r < carry) break;
         }

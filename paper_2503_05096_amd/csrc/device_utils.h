@@ -119,6 +119,14 @@ __device__ __forceinline__ ArgMax wave_argmax(ArgMax a)
     return a;
 }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also drains the
+// vector-memory counter (its fences cover global memory), which would stall on every global load
+// that was deliberately left in flight across the barrier; this one waits for LDS traffic alone.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ __forceinline__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
