@@ -77,6 +77,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4g", "cfg5"])
     ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="run only a plain 512 MiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -84,6 +86,16 @@ def main() -> int:
         return 2
 
     import torch
+    if args.calibration_copy:
+        nbytes = 512 << 20
+        src = torch.ones(nbytes, dtype=torch.uint8, device="cuda:0")
+        dst = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_bytes": nbytes, "copies": 3}))
+        return 0
     import workloads as W
     import paper_2503_05096_amd as pkg
     from tests.harness import to_device
