@@ -65,6 +65,7 @@ struct FastScratch {
     double tau, before;
     int    itstar, retry;
     int    row_i, row_j, row_k;
+    float  row_T;
     int    first_hit, last_pos;
 };
 
@@ -94,13 +95,35 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)tid16, it * (kFT * 16), 0);
         return make_uint4(v.x, v.y, v.z, v.w);
     };
+    // Chunks past the end of the row arrive as zeros (buffer range check) and must count as -inf:
+    // OR-ing the -inf pattern into them is branch-free and in place, one chunk at a time right before
+    // its first use, so that no step waits for data it does not need yet.
+    auto blank_tail = [&](uint4 &v, int it) {
+        const uint32_t ninf = (it * kFT + tid >= nchunks) ? P::kNegInf2 : 0u;
+        // (in assembly so that the result stays in the registers the load wrote: as plain C the
+        // compiler keeps blanked copies next to the originals and runs out of registers)
+        asm volatile("v_or_b32 %0, %0, %4\n\tv_or_b32 %1, %1, %4\n\tv_or_b32 %2, %2, %4\n\tv_or_b32 %3, %3, %4"
+                     : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w) : "v"(ninf));
+    };
     // (the first 1024 draft lengths are requested ahead of the row: the memory counter is in order,
     // so anything asked for after the row would only be seen once the whole row has arrived)
     int n_first = 0;
-    if (tid < B) n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
+    float t_first = 0.f;
+    if (tid < B) {
+        n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
+        t_first = temperature[tid];           // the owner of the row's request publishes it with (i, j, k)
+    }
+    // Only the first kLPre steps of the row are requested here.  A wavefront executes in order and a
+    // load instruction is held back while the memory pipeline of the compute unit is full, so a
+    // wavefront that asks for its whole share at once does nothing else until most of it has
+    // arrived; the rest is requested step by step inside the sweep below.
+    constexpr int kLPre = ITER < 8 ? ITER : 8;
     uint4 lg[ITER];
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) lg[it] = load_chunk(rl, it);
+    for (int it = 0; it < kLPre; ++it) {
+        lg[it] = load_chunk(rl, it);
+        __builtin_amdgcn_sched_barrier(0);    // issue in step order: the sweep consumes them in that order
+    }
 
     // ---- which request owns row r?  (while the loads travel)  Block scan of n_i = k_i + 1 over the
     // requests, 1024 at a time; the thread whose request covers r publishes (i, j, k).
@@ -109,7 +132,11 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         for (int base = 0; base < B; base += kFT) {
             const int i = base + tid;
             int n = n_first;
-            if (base > 0) n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+            float tt = t_first;
+            if (base > 0) {
+                n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+                tt = i < B ? temperature[i] : 0.f;
+            }
             const int inc = wave_scan_incl(n, lane);
             if (lane == 63) sm.ai[wv] = inc;
             lds_barrier();           // LDS only: the row's loads stay in flight
@@ -120,7 +147,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
                 tot += sm.ai[w];
             }
             const int start = pre + inc - n;
-            if (r >= start && r < start + n) { sm.row_i = i; sm.row_j = r - start; sm.row_k = n - 1; }
+            if (r >= start && r < start + n) { sm.row_i = i; sm.row_j = r - start; sm.row_k = n - 1; sm.row_T = tt; }
             lds_barrier();           // LDS only: the row's loads stay in flight
             carry = tot;
             if (r < carry) break;
@@ -129,28 +156,23 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     const int ri = __builtin_amdgcn_readfirstlane(sm.row_i), j = __builtin_amdgcn_readfirstlane(sm.row_j),
               k = __builtin_amdgcn_readfirstlane(sm.row_k);   // wave-uniform: the loads below are scalar
     const bool bonus = j >= k;
-    const float T = temperature[ri];
-    const int x = bonus ? -1 : draft_tokens[r - ri];
+    const float T = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm.row_T)));
     const char *prow = probs + (int64_t)(r - ri) * pstride * 2;
-    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, V * 2, 0x00020000);
     const bool sampled = T != 0.0f;
     const bool has_q = sampled && !bonus;
+    // A row without draft probabilities (bonus row, q == 0) gets a descriptor of size zero: its loads
+    // return zeros without touching memory.  So the stream below is unconditional and the number of
+    // loads in flight is the same on every path, which lets each wait name exactly the chunk it needs.
+    __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, has_q ? V * 2 : 0, 0x00020000);
     uint4 qb[kQPre];
-    if (has_q) {
-#pragma unroll
-        for (int it = 0; it < kQPre && it < ITER; ++it) qb[it] = load_chunk(rq, it);
-    }
-#pragma unroll
-    for (int it = 0; it < ITER; ++it)
-        if ((it + 1) * kFT > nchunks && it * kFT + tid >= nchunks)
-            lg[it] = make_uint4(P::kNegInf2, P::kNegInf2, P::kNegInf2, P::kNegInf2);
-
     if (!sampled) {
         // greedy: argmax with the lowest index on ties (elements are visited in index order per thread)
         ArgMax best{-INFINITY, V};
 #pragma unroll
+        for (int it = kLPre; it < ITER; ++it) lg[it] = load_chunk(rl, it);
+#pragma unroll
         for (int it = 0; it < ITER; ++it) {
-            keep_packed(lg[it]);
+            blank_tail(lg[it], it);
             const uint32_t *w = &lg[it].x;
             const int base = (it * kFT + tid) * 8;
 #pragma unroll
@@ -168,35 +190,64 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             ArgMax a{sm.av[0], sm.ai[0]};
             for (int w = 1; w < kFW; ++w) a = argmax_merge(a, ArgMax{sm.av[w], sm.ai[w]});
             if (a.i >= V) a.i = 0;
-            row_flag[r] = bonus ? 1 : (x == a.i);
+            row_flag[r] = bonus ? 1 : (draft_tokens[r - ri] == a.i);
             row_cand[r] = a.i;
         }
         return;
     }
 
-    // ---- 2. maximum and normaliser ---------------------------------------------------------
-    // Both 16-bit formats are sign-magnitude, so a packed SIGNED 16-bit integer maximum started at
-    // +0 yields max(0, largest positive logit) with one instruction per two elements.  A row
-    // without any positive logit (block result 0) takes the exact float maximum instead.
+    // ---- 2. maximum and normaliser, in ONE sweep, step by step as the loads land ----------------
+    // The vector ALUs would idle while the row travels, so the normaliser is accumulated on line
+    // against a running per-thread reference m_run = max(0, largest logit seen so far).  Both 16-bit
+    // formats are sign-magnitude, so a packed SIGNED 16-bit integer maximum started at +0 tracks it
+    // with one instruction per two elements; when it grows, the partial sum is rescaled (one extra
+    // exponential per 8-element chunk).  Thread, wavefront and block results are combined as (m, z)
+    // pairs.  A row without any positive logit (block maximum 0) is redone with the exact maximum.
     const float c = 1.4426950408889634f / T;
     short2v pm = {0, 0};
+    float m_run = 0.f, zt = 0.f;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
+        // keep the memory pipeline fed: the row's step it + kLPre, then the first steps of the
+        // draft-probability row (they are consumed by the streaming pass further down)
+        if (it + kLPre < ITER) lg[it + kLPre] = load_chunk(rl, it + kLPre);
+        else if (it + kLPre - ITER < kQPre) qb[it + kLPre - ITER] = load_chunk(rq, it + kLPre - ITER);
+        blank_tail(lg[it], it);
+        keep_packed(lg[it]);
         const uint32_t *w = &lg[it].x;
 #pragma unroll
         for (int e = 0; e < 4; ++e) pm = __builtin_elementwise_max(pm, __builtin_bit_cast(short2v, w[e]));
+        const float mn = P::lo((uint32_t)(uint16_t)max(pm.x, pm.y));
+        zt *= __builtin_amdgcn_exp2f((m_run - mn) * c);
+        m_run = mn;
+        const float mnc = mn * c;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            zt += __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mnc));
+            zt += __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mnc));
+            if (e == 1) __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
+    // The draft token is asked for only now (scalar load): scalar loads and LDS reads share one
+    // counter that cannot tell them apart, so an earlier request would have made the temperature
+    // above wait for this load as well.  It arrives while the block result is being exchanged.
+    __builtin_amdgcn_sched_barrier(0);
+    const int x = bonus ? -1 : draft_tokens[r - ri];
     {
-        const int mw = wave_max(max((int)pm.x, (int)pm.y));
-        if (lane == 0) sm.ai[wv] = mw;
+        const float mw = wave_max(m_run);
+        const float zw = wave_sum(zt * __builtin_amdgcn_exp2f((m_run - mw) * c));
+        if (lane == 0) { sm.wm[wv] = mw; sm.wz[wv] = zw; }
         if (tid == 0) { sm.first_hit = kFT; sm.last_pos = -1; }
     }
-    __syncthreads();
-    int mbits = sm.ai[0];
+    lds_barrier();
+    float m = sm.wm[0];
 #pragma unroll
-    for (int w = 1; w < kFW; ++w) mbits = max(mbits, sm.ai[w]);
-    float m = P::lo((uint32_t)mbits);
-    if (mbits == 0) {                         // rare: no positive logit in the row
+    for (int w = 1; w < kFW; ++w) m = fmaxf(m, sm.wm[w]);
+    double Zd = 0.0;
+#pragma unroll
+    for (int w = 0; w < kFW; ++w) Zd += (double)(sm.wz[w] * __builtin_amdgcn_exp2f((sm.wm[w] - m) * c));
+    if (m == 0.f) {                           // rare: no positive logit in the row -> exact two-sweep form
         float mt = -INFINITY;
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {
@@ -207,45 +258,47 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
         mt = wave_max(mt);
+        lds_barrier();                        // everyone has read wm / wz
         if (lane == 0) sm.wm[wv] = mt;
-        __syncthreads();
+        lds_barrier();
         m = sm.wm[0];
 #pragma unroll
         for (int w = 1; w < kFW; ++w) m = fmaxf(m, sm.wm[w]);
-    }
-    // e_v = 2^(l_v * c - m * c): the same fused expression everywhere, so Z and every p_v agree
-    const float mc = m * c;
-    float zt = 0.f;
+        const float mc0 = m * c;
+        float z2 = 0.f;
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-        keep_packed(lg[it]);
-        const uint32_t *w = &lg[it].x;
+        for (int it = 0; it < ITER; ++it) {
+            keep_packed(lg[it]);
+            const uint32_t *w = &lg[it].x;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            zt += __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mc));
-            zt += __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mc));
-            if (e == 1) __builtin_amdgcn_sched_barrier(0);
+            for (int e = 0; e < 4; ++e) {
+                z2 += __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c, -mc0));
+                z2 += __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c, -mc0));
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    zt = wave_sum(zt);
-    if (lane == 0) sm.wz[wv] = zt;
-    __syncthreads();
-    double Zd = 0.0;
+        z2 = wave_sum(z2);
+        if (lane == 0) sm.wz[wv] = z2;
+        lds_barrier();
+        Zd = 0.0;
 #pragma unroll
-    for (int w = 0; w < kFW; ++w) Zd += (double)sm.wz[w];
+        for (int w = 0; w < kFW; ++w) Zd += (double)sm.wz[w];
+    }
+    // e_v = 2^(l_v * c - m * c) from here on: one fused expression for the accept test, the residual
+    // sums and the final search, so that all of them see the same p_v = e_v / Z
+    const float mc = m * c;
     const float invZ = (float)(1.0 / Zd);
 
-    if (tid == 0) {
-        int flag = 1;
-        if (!bonus) {
-            const uint16_t lb = *reinterpret_cast<const uint16_t *>(lrow + (int64_t)x * 2);
-            const uint16_t qx16 = *reinterpret_cast<const uint16_t *>(prow + (int64_t)x * 2);
-            const float lx = P::lo(lb), qx = P::lo(qx16);
-            const float px = __builtin_amdgcn_exp2f(fmaf(lx, c, -mc)) * invZ;
-            flag = (qx > 0.f) ? (uniforms[2 * (int64_t)r] < px / qx) : 1;
-        }
-        row_flag[r] = flag;
+    // accept test, first half.  x is the same for the whole workgroup, so l_x and q_x come by scalar
+    // loads (aligned 32-bit words holding the 16-bit values): they do not queue behind the vector
+    // loads of the draft-probability stream.  They are requested here and used after the streaming
+    // pass, so nobody waits for them.
+    uint32_t lw_x = 0, qw_x = 0;
+    float u_acc = 0.f;
+    if (!bonus) {
+        lw_x = reinterpret_cast<const uint32_t *>(lrow)[x >> 1];
+        qw_x = reinterpret_cast<const uint32_t *>(prow)[x >> 1];
+        u_acc = uniforms[2 * (int64_t)r];
     }
 
     // ---- 3./4. residual mass per step, block totals, the step that holds tau ------------------
@@ -253,11 +306,8 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     for (int attempt = 0; attempt < 2; ++attempt) {
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {
-            uint4 qv = make_uint4(0, 0, 0, 0);
-            if (use_q) {
-                qv = qb[it % kQPre];
-                if (it + kQPre < ITER) qb[it % kQPre] = load_chunk(rq, it + kQPre);
-            }
+            const uint4 qv = qb[it % kQPre];
+            if (it + kQPre < ITER) qb[it % kQPre] = load_chunk(rq, it + kQPre);
             keep_packed(lg[it]);
             const uint32_t *w = &lg[it].x, *qw = &qv.x;
             float acc = 0.f;
@@ -309,9 +359,23 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         if (!sm.retry) break;
         // p == q everywhere (R == 0): draw from p instead; the q row is not read on the second pass
         use_q = false;
+        rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(prow), 0, 0, 0x00020000);
+#pragma unroll
+        for (int it = 0; it < kQPre; ++it) qb[it] = make_uint4(0, 0, 0, 0);
         __syncthreads();
     }
     const double tau = sm.tau, before = sm.before;
+
+    if (tid == 0) {                           // accept test, second half
+        int flag = 1;
+        if (!bonus) {
+            const float lx = (x & 1) ? P::hi(lw_x) : P::lo(lw_x);
+            const float qx = (x & 1) ? P::hi(qw_x) : P::lo(qw_x);
+            const float px = __builtin_amdgcn_exp2f(fmaf(lx, c, -mc)) * invZ;
+            flag = (qx > 0.f) ? (u_acc < px / qx) : 1;
+        }
+        row_flag[r] = flag;
+    }
 
     // ---- 5. inside step it*: the owning thread, then the element --------------------------------
     const int itstar = __builtin_amdgcn_readfirstlane(sm.itstar);
@@ -320,8 +384,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     for (int it = 1; it < ITER; ++it)
         if (it == itstar) lstar = lg[it];
     const int cstar = itstar * kFT + tid;
-    uint4 qstar = make_uint4(0, 0, 0, 0);
-    if (use_q) qstar = load_chunk(rq, itstar);
+    const uint4 qstar = load_chunk(rq, itstar);
     float rv[8], sstar = 0.f;
     {
         const uint32_t *w = &lstar.x, *qw = &qstar.x;

@@ -447,8 +447,9 @@ hipError_t launch_attn_mfma(const AttnArgs &a)
         if (slots == 0) {
             int dev = 0, cus = 256, per_cu = 1;
             if (hipGetDevice(&dev) == hipSuccess) {
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0);
+                if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+                if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0) != hipSuccess)
+                    per_cu = 1;
             }
             slots = cus * (per_cu > 0 ? per_cu : 1);
         }
