@@ -57,8 +57,7 @@ __device__ __forceinline__ float row16_sum(float v)
 }
 
 struct FastScratch {
-    float  sw[kFW][16][4];   // per step: the four 16-lane row sums of every wavefront
-    double st[16];           // block totals of every step
+    alignas(16) float sw[kFW][16][4];   // per step: the four 16-lane row sums of every wavefront
     float  wm[kFW], wz[kFW];
     float  av[kFW];
     int    ai[kFW];
@@ -294,11 +293,10 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     // loads of the draft-probability stream.  They are requested here and used after the streaming
     // pass, so nobody waits for them.
     uint32_t lw_x = 0, qw_x = 0;
-    float u_acc = 0.f;
+    const float u_acc = uniforms[2 * (int64_t)r], u_draw = uniforms[2 * (int64_t)r + 1];
     if (!bonus) {
         lw_x = reinterpret_cast<const uint32_t *>(lrow)[x >> 1];
         qw_x = reinterpret_cast<const uint32_t *>(prow)[x >> 1];
-        u_acc = uniforms[2 * (int64_t)r];
     }
 
     // ---- 3./4. residual mass per step, block totals, the step that holds tau ------------------
@@ -323,39 +321,33 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             if ((lane & 15) == 0) sm.sw[wv][it][lane >> 4] = acc;
             __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
-        if (tid < ITER) {
+        lds_barrier();
+        if (wv == 0) {
+            // One wavefront finishes the reduction: lane L owns step L (16 wavefronts x 4 row sums each,
+            // added in fp64), an inclusive scan over the lanes gives the running totals, R is the
+            // last of them, and the step that holds tau = u1 * R is the first lane whose running
+            // total exceeds it.
             double t = 0.0;
-#pragma unroll 1
-            for (int w = 0; w < kFW; ++w)
-                t = t + (((double)sm.sw[w][tid][0] + (double)sm.sw[w][tid][1]) +
-                         ((double)sm.sw[w][tid][2] + (double)sm.sw[w][tid][3]));
-            sm.st[tid] = t;
-        }
-        __syncthreads();
-        if (tid == 0) {                       // running totals over the steps: R, tau and the step holding tau
-            double R = 0.0;
-#pragma unroll 1
-            for (int it = 0; it < ITER; ++it) R = R + sm.st[it];
-            const double tq = (double)uniforms[2 * (int64_t)r + 1] * R;
-            double run = 0.0, bef = 0.0;
-            int pick = -1;
-#pragma unroll 1
-            for (int it = 0; it < ITER; ++it) {
-                const double nxt = run + sm.st[it];
-                if (pick < 0 && nxt > tq) { pick = it; bef = run; }
-                run = nxt;
+            if (lane < ITER) {
+#pragma unroll
+                for (int w = 0; w < kFW; ++w) {
+                    const float4 v = *reinterpret_cast<const float4 *>(sm.sw[w][lane]);
+                    t = t + (((double)v.x + (double)v.y) + ((double)v.z + (double)v.w));
+                }
             }
-            if (pick < 0) {                   // cannot happen for u1 < 1; keep the result defined
-                pick = ITER - 1;
-                bef = 0.0;
-#pragma unroll 1
-                for (int it = 0; it < ITER - 1; ++it) bef = bef + sm.st[it];
+            const double incl = wave_scan_incl(t, lane);
+            const double R = __shfl(incl, ITER - 1, kWave);
+            const double tq = (double)u_draw * R;
+            const unsigned long long hits = __ballot(lane < ITER && incl > tq);
+            // (no lane can only happen through rounding at u1 -> 1: take the last step)
+            const int pick = hits ? (int)__builtin_ctzll(hits) : ITER - 1;
+            const double bef = __shfl(incl - t, pick, kWave);
+            if (lane == 0) {
+                sm.tau = tq; sm.before = bef; sm.itstar = pick;
+                sm.retry = !(R > 0.0) && use_q;
             }
-            sm.tau = tq; sm.before = bef; sm.itstar = pick;
-            sm.retry = !(R > 0.0) && use_q;
         }
-        __syncthreads();
+        lds_barrier();
         if (!sm.retry) break;
         // p == q everywhere (R == 0): draw from p instead; the q row is not read on the second pass
         use_q = false;
@@ -385,6 +377,20 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
         if (it == itstar) lstar = lg[it];
     const int cstar = itstar * kFT + tid;
     const uint4 qstar = load_chunk(rq, itstar);
+    // residual mass ahead of this wavefront inside step it*: lane L adds up wavefront L's four row
+    // sums, a scan over the lanes gives the prefixes (done while the chunk above travels)
+    double base = before;
+    {
+        double ws = 0.0;
+        if (lane < kFW) {
+            const float4 v = *reinterpret_cast<const float4 *>(sm.sw[lane][itstar]);
+            ws = ((double)v.x + (double)v.y) + ((double)v.z + (double)v.w);
+        }
+        const double wincl = wave_scan_incl(ws, lane);
+        const double ahead = __shfl(wincl, max(wv - 1, 0), kWave);
+        if (wv > 0) base = base + ahead;
+    }
+    __builtin_amdgcn_sched_barrier(0);
     float rv[8], sstar = 0.f;
     {
         const uint32_t *w = &lstar.x, *qw = &qstar.x;
@@ -398,11 +404,6 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             sstar += rv[2 * e + 1];
         }
     }
-    double base = before;
-#pragma unroll 1
-    for (int w = 0; w < wv; ++w)
-        base = base + (((double)sm.sw[w][itstar][0] + (double)sm.sw[w][itstar][1]) +
-                       ((double)sm.sw[w][itstar][2] + (double)sm.sw[w][itstar][3]));
     const double wi = wave_scan_incl((double)sstar, lane);
     double we = __shfl_up(wi, 1, kWave);
     if (lane == 0) we = 0.0;
