@@ -178,6 +178,60 @@ int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_l
                                 int32_t *err_flags, void *stream);
 
 /* ------------------------------------------------------------------------
+ * The two steps on either side of a verification step (paper Sec. 6: the
+ * target model's KV cache is paged, and the results of one speculative step
+ * are integrated into the input of the next).
+ *
+ * adaspec_kv_append - BEFORE verification: scatter the K and V rows of the n_i
+ * new tokens of every request (the last committed token and its k_i drafts)
+ * into the pages.  Row j of request i goes to position pos = ctx_lens[i] - n_i + j:
+ * page block_table[i][pos / P], slot pos % P, every kv head.
+ *   k_new, v_new [TQ][Hkv][d] of dims->dtype, request-major rows like q
+ *   k_pages, v_pages are updated in place; nothing else in them is touched.
+ * Uses of dims: batch, total_q, max_spec_len, n_kv_heads, head_dim (a multiple
+ * of 8 for 16-bit types, of 4 for fp32), page_size, num_pages,
+ * max_pages_per_req, dtype; the other fields are ignored.  All four tensors
+ * must be 16-byte aligned.  Needs no workspace.
+ * ---------------------------------------------------------------------- */
+int adaspec_kv_append(const void *k_new, const void *v_new, void *k_pages, void *v_pages,
+                      const int32_t *block_table, const int32_t *ctx_lens,
+                      const int32_t *spec_lens, const adaspec_attn_dims *dims, void *stream);
+
+/*
+ * adaspec_commit - AFTER acceptance: keep what was accepted, drop the rest.
+ * Request i had L_i = ctx_lens[i] cached tokens including its n_i = k_i + 1 new
+ * ones and accepted a_i = out_accept_len[i] drafts.  The cache entries of the
+ * last committed token and of the a_i accepted drafts stay; the k_i - a_i
+ * rejected ones become dead slots (they are overwritten by later appends).
+ * The recovered / bonus token out_tokens[i][a_i] has no cache entry yet: it is
+ * row 0 of the next step.
+ *   committed_lens [B]  = L_i - k_i + a_i                      (cache length kept)
+ *   next_ctx_lens  [B]  = committed_lens[i] + next_spec_lens[i] + 1, i.e. the
+ *                         ctx_lens of the next step; written only if both
+ *                         next_spec_lens and next_ctx_lens are non-NULL
+ *   last_token     [B]  = out_tokens[i][a_i]
+ *   seq_tokens [B][seq_stride], seq_lens [B] (both NULL, or both non-NULL): the
+ *                         a_i + 1 emitted tokens are appended at seq_lens[i] and
+ *                         seq_lens[i] grows by a_i + 1; tokens that do not fit
+ *                         in seq_stride are dropped and seq_lens[i] stops at
+ *                         seq_stride.
+ * committed_lens may alias ctx_lens (in-place update).
+ */
+typedef struct {
+    int32_t batch;          /* B                                     */
+    int32_t max_spec_len;   /* upper bound on spec_lens[i]           */
+    int32_t out_stride;     /* row stride of out_tokens              */
+    int32_t seq_stride;     /* row stride of seq_tokens (0 if unused) */
+} adaspec_commit_dims;
+
+int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
+                   const int32_t *spec_lens, const int32_t *ctx_lens,
+                   const int32_t *next_spec_lens,
+                   int32_t *committed_lens, int32_t *next_ctx_lens, int32_t *last_token,
+                   int32_t *seq_tokens, int32_t *seq_lens,
+                   const adaspec_commit_dims *dims, void *stream);
+
+/* ------------------------------------------------------------------------
  * Per-kernel timing for benchmarks: when both events are non-NULL, the next
  * calls record `start` (hipEvent_t) right before and `stop` right after the
  * launch of the selected kernel on the call's stream.  Pass NULLs to clear.

@@ -20,7 +20,8 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST}
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
     "adaspec_accept_workspace_bytes", "adaspec_accept",
-    "adaspec_check_ragged_inputs", "adaspec_set_timing_events",
+    "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
+    "adaspec_set_timing_events",
     "adaspec_status_string", "adaspec_version",
 )
 
@@ -39,6 +40,11 @@ class AcceptDims(C.Structure):
                 ("probs_dtype", C.c_int32), ("out_stride", C.c_int32),
                 ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64),
                 ("path", C.c_int32), ("reserved", C.c_int32)]
+
+
+class CommitDims(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("max_spec_len", C.c_int32), ("out_stride", C.c_int32),
+                ("seq_stride", C.c_int32)]
 
 
 class AdaspecError(RuntimeError):
@@ -70,6 +76,10 @@ def lib() -> C.CDLL:
         L.adaspec_accept.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
         L.adaspec_check_ragged_inputs.restype = C.c_int
         L.adaspec_check_ragged_inputs.argtypes = [vp, vp, vp, C.POINTER(AttnDims), vp, vp]
+        L.adaspec_kv_append.restype = C.c_int
+        L.adaspec_kv_append.argtypes = [vp] * 7 + [C.POINTER(AttnDims), vp]
+        L.adaspec_commit.restype = C.c_int
+        L.adaspec_commit.argtypes = [vp] * 10 + [C.POINTER(CommitDims), vp]
         L.adaspec_set_timing_events.restype = C.c_int
         L.adaspec_set_timing_events.argtypes = [C.c_int, vp, vp]
         L.adaspec_status_string.restype = C.c_char_p
@@ -207,6 +217,58 @@ def check_ragged_inputs(block_table, ctx_lens, spec_lens, dims: AttnDims, stream
     if rc != 0:
         raise AdaspecError(rc, "adaspec_check_ragged_inputs")
     return int(flags.item())
+
+
+def kv_append(k_new, v_new, k_pages, v_pages, block_table, ctx_lens, spec_lens, *, max_spec_len: int,
+              stream=None) -> None:
+    """adaspec_kv_append: writes the new tokens' K/V rows [TQ][Hkv][d] into the pages, in place."""
+    import torch
+    TQ, Hkv, d = k_new.shape
+    num_pages, Hkv2, P, d2 = k_pages.shape
+    B, max_pages = block_table.shape
+    assert (Hkv2, d2) == (Hkv, d) and v_new.shape == k_new.shape and v_pages.shape == k_pages.shape
+    assert k_new.dtype == v_new.dtype == k_pages.dtype == v_pages.dtype
+    for t in (k_new, v_new, k_pages, v_pages, block_table, ctx_lens, spec_lens):
+        assert t.is_cuda and t.is_contiguous()
+    assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32 and spec_lens.dtype == torch.int32
+    dt = _dtype_code(k_new)
+    dims = AttnDims(B, TQ, int(max_spec_len), Hkv, Hkv, d, P, num_pages, max_pages, dt, dt, PATH_AUTO, 0.0)
+    rc = lib().adaspec_kv_append(k_new.data_ptr(), v_new.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+                                 block_table.data_ptr(), ctx_lens.data_ptr(), spec_lens.data_ptr(),
+                                 C.byref(dims), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_kv_append")
+
+
+def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, *, max_spec_len: int, next_spec_lens=None,
+           committed_lens=None, next_ctx_lens=None, last_token=None, seq_tokens=None, seq_lens=None,
+           stream=None):
+    """adaspec_commit; returns (committed_lens, next_ctx_lens or None, last_token)."""
+    import torch
+    B, out_stride = out_tokens.shape
+    dev = out_tokens.device
+    for t in (out_tokens, out_accept_len, spec_lens, ctx_lens):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int32
+    if committed_lens is None:
+        committed_lens = torch.empty((B,), dtype=torch.int32, device=dev)
+    if last_token is None:
+        last_token = torch.empty((B,), dtype=torch.int32, device=dev)
+    if next_spec_lens is not None and next_ctx_lens is None:
+        next_ctx_lens = torch.empty((B,), dtype=torch.int32, device=dev)
+    seq_stride = 0
+    if seq_tokens is not None:
+        assert seq_lens is not None and seq_tokens.is_contiguous() and seq_tokens.dtype == torch.int32
+        assert seq_lens.dtype == torch.int32
+        seq_stride = seq_tokens.shape[1]
+    dims = CommitDims(B, int(max_spec_len), out_stride, seq_stride)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    rc = lib().adaspec_commit(out_tokens.data_ptr(), out_accept_len.data_ptr(), spec_lens.data_ptr(),
+                              ctx_lens.data_ptr(), ptr(next_spec_lens), committed_lens.data_ptr(),
+                              ptr(next_ctx_lens), last_token.data_ptr(), ptr(seq_tokens), ptr(seq_lens),
+                              C.byref(dims), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_commit")
+    return committed_lens, next_ctx_lens, last_token
 
 
 def set_timing_events(which: int, start_event_ptr: Optional[int], stop_event_ptr: Optional[int]) -> None:

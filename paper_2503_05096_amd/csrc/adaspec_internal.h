@@ -92,4 +92,13 @@ hipError_t launch_check_ragged(const int32_t *block_table, const int32_t *ctx_le
                                const int32_t *spec_lens, const adaspec_attn_dims &d,
                                int32_t *err_flags, hipStream_t stream);
 
+hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_pages, void *v_pages,
+                            const int32_t *block_table, const int32_t *ctx_lens,
+                            const int32_t *spec_lens, const adaspec_attn_dims &d, hipStream_t stream);
+hipError_t launch_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
+                         const int32_t *spec_lens, const int32_t *ctx_lens,
+                         const int32_t *next_spec_lens, int32_t *committed_lens,
+                         int32_t *next_ctx_lens, int32_t *last_token, int32_t *seq_tokens,
+                         int32_t *seq_lens, const adaspec_commit_dims &d, hipStream_t stream);
+
 }  // namespace adaspec

@@ -209,6 +209,50 @@ int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_l
     return ADASPEC_OK;
 }
 
+int adaspec_kv_append(const void *k_new, const void *v_new, void *k_pages, void *v_pages,
+                      const int32_t *block_table, const int32_t *ctx_lens,
+                      const int32_t *spec_lens, const adaspec_attn_dims *d, void *stream)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->batch < 0 || d->total_q < d->batch || d->max_spec_len < 0) return ADASPEC_ERR_DIM;
+    if ((int64_t)d->total_q > (int64_t)d->batch * (d->max_spec_len + 1)) return ADASPEC_ERR_DIM;
+    if (d->n_kv_heads <= 0 || d->head_dim <= 0 || d->page_size <= 0) return ADASPEC_ERR_DIM;
+    if (d->num_pages <= 0 || d->max_pages_per_req <= 0) return ADASPEC_ERR_DIM;
+    if (!dtype_ok(d->dtype)) return ADASPEC_ERR_DTYPE;
+    if ((d->head_dim * (d->dtype == ADASPEC_F32 ? 4 : 2)) % 16) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->batch == 0) return ADASPEC_OK;
+    if (!k_new || !v_new || !k_pages || !v_pages || !block_table || !ctx_lens || !spec_lens)
+        return ADASPEC_ERR_NULL;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pages) || !aligned16(v_pages))
+        return ADASPEC_ERR_ALIGN;
+    if (launch_kv_append(k_new, v_new, k_pages, v_pages, block_table, ctx_lens, spec_lens, *d,
+                         static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
+                   const int32_t *spec_lens, const int32_t *ctx_lens,
+                   const int32_t *next_spec_lens,
+                   int32_t *committed_lens, int32_t *next_ctx_lens, int32_t *last_token,
+                   int32_t *seq_tokens, int32_t *seq_lens,
+                   const adaspec_commit_dims *d, void *stream)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->batch < 0 || d->max_spec_len < 0 || d->seq_stride < 0) return ADASPEC_ERR_DIM;
+    if (d->out_stride < d->max_spec_len + 1) return ADASPEC_ERR_DIM;
+    if ((seq_tokens == nullptr) != (seq_lens == nullptr)) return ADASPEC_ERR_NULL;
+    if (seq_tokens && d->seq_stride <= 0) return ADASPEC_ERR_DIM;
+    if (d->batch == 0) return ADASPEC_OK;
+    if (!out_tokens || !out_accept_len || !spec_lens || !ctx_lens || !committed_lens || !last_token)
+        return ADASPEC_ERR_NULL;
+    if (launch_commit(out_tokens, out_accept_len, spec_lens, ctx_lens, next_spec_lens, committed_lens,
+                      next_ctx_lens, last_token, seq_tokens, seq_lens, *d,
+                      static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
 int adaspec_set_timing_events(int which, void *start_event, void *stop_event)
 {
     if (which < 0 || which > 1) return ADASPEC_ERR_DIM;

@@ -131,6 +131,31 @@ def test_misc_entry_points_validate():
     assert "unknown" in pkg.status_string(-99)
 
 
+def test_kv_append_and_commit_validate():
+    from paper_2503_05096_amd.binding import CommitDims
+    L = pkg.lib()
+    d = _attn_dims()
+    assert L.adaspec_kv_append(PTR, PTR, PTR, PTR, PTR, PTR, PTR, None, None) == -1
+    assert L.adaspec_kv_append(None, PTR, PTR, PTR, PTR, PTR, PTR, C.byref(d), None) == -1
+    assert L.adaspec_kv_append(PTR + 4, PTR, PTR, PTR, PTR, PTR, PTR, C.byref(d), None) == -4
+    assert L.adaspec_kv_append(PTR, PTR, PTR, PTR, PTR, PTR, PTR, C.byref(_attn_dims(n_kv_heads=0)), None) == -2
+    assert L.adaspec_kv_append(PTR, PTR, PTR, PTR, PTR, PTR, PTR, C.byref(_attn_dims(dtype=7)), None) == -3
+    assert L.adaspec_kv_append(PTR, PTR, PTR, PTR, PTR, PTR, PTR, C.byref(_attn_dims(head_dim=4, dtype=BF16)), None) == -6
+    assert L.adaspec_kv_append(None, None, None, None, None, None, None, C.byref(_attn_dims(batch=0, total_q=0)), None) == 0
+    c = CommitDims(4, 3, 4, 0)
+    args = [PTR] * 4 + [None] + [PTR, None, PTR, None, None]
+    assert L.adaspec_commit(*args, None, None) == -1
+    assert L.adaspec_commit(*args, C.byref(CommitDims(4, 3, 3, 0)), None) == -2      # out_stride < k_max + 1
+    assert L.adaspec_commit(*args, C.byref(CommitDims(-1, 3, 4, 0)), None) == -2
+    bad = list(args); bad[0] = None
+    assert L.adaspec_commit(*bad, C.byref(c), None) == -1
+    half = list(args); half[8] = PTR                                                  # seq_tokens without seq_lens
+    assert L.adaspec_commit(*half, C.byref(c), None) == -1
+    both = list(args); both[8] = PTR; both[9] = PTR
+    assert L.adaspec_commit(*both, C.byref(c), None) == -2                            # seq_stride 0
+    assert L.adaspec_commit(*[None] * 10, C.byref(CommitDims(0, 3, 4, 0)), None) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2503_05096_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
