@@ -1,4 +1,5 @@
-"""Builds libadaspec.so (the C-ABI library) from csrc/*.hip for gfx950 with hipcc."""
+"""Builds libadaspec.so (the C-ABI library) from csrc/*.hip (device + host code) and csrc/*.cpp
+(host-only code) for gfx950 with hipcc."""
 from __future__ import annotations
 
 import glob
@@ -9,6 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libadaspec.so")
 
@@ -22,12 +24,12 @@ FLAGS = [
 
 def build_library(verbose: bool = False, jobs: int = 8) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    objects = [os.path.join(BUILD_DIR, os.path.basename(s)[:-4] + ".o") for s in sources]
+    sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
+    objects = [os.path.join(BUILD_DIR, os.path.basename(s).replace(".", "_") + ".o") for s in sources]
 
     def compile_one(pair):
         src, obj = pair
-        cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+        cmd = [HIPCC, *FLAGS, "-I", INCLUDE, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -226,3 +226,22 @@ def test_ragged_input_check(pkg):
     assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, sp, dims) & 8
     sp[1] = 9
     assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, sp, dims) & 1
+
+
+def test_policy_shaped_raggedness(oracle_mod, pkg):
+    """spec_lens produced by the speculative-length policy itself (adaptive drafter, then draft-token
+    elimination, driven by synthetic draft confidences) instead of a hand-set distribution."""
+    from paper_2503_05096_amd import policy as PP
+    rng = np.random.default_rng(17)
+    B, SL = 48, 6
+    C = np.clip(np.round(np.exp(np.log(1024) + 0.7 * rng.standard_normal(B))), 128, 4096).astype(np.int32)
+    conf = rng.beta(4, 2, (SL, B))
+    model = PP.TimeModel(2e-8, 2e-6, 1.5e-3, 7e-8, 2e-5, 6e-3)
+    steps, ar, _ = PP.adaptive_draft(model, C, conf, prev_conf=0.7)
+    k, _ = PP.eliminate(model, C, steps, ar)
+    assert steps == SL and k.min() < k.max() and k.max() <= SL            # genuinely ragged
+    st = W.make_custom_step(170, ctx_lens=(C + k + 1).astype(np.int32), spec_lens=k, n_q_heads=32, n_kv_heads=8,
+                            head_dim=128, dtype="bf16", vocab=32000, logits_dtype="bf16", temperature=0.8,
+                            logits_sigma=3.0, noise_sigma=1.5, draft_temp=1.2, name="policy-shaped")
+    check_attention(st, oracle_mod, pkg)
+    check_accept(st, oracle_mod, pkg)
