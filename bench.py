@@ -27,7 +27,8 @@ class HipEvents:
     """Raw hipEvent_t pairs (the library records them around its main kernel)."""
 
     def __init__(self, n: int):
-        self.hip = C.CDLL("libamdhip64.so")
+        import paper_2503_05096_amd as pkg
+        self.hip = pkg.binding.hip_runtime()           # the one runtime torch and the library share
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         self.hip.hipEventSynchronize.argtypes = [C.c_void_p]

@@ -64,6 +64,11 @@ def lib() -> C.CDLL:
             raise ImportError(
                 f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; "
                 "g.build()' or python paper_2503_05096_amd/build.py). There is no fallback path.")
+        # The process must hold ONE HIP runtime.  PyTorch ships its own copy and loads it by path;
+        # the loader shares it with this library only if it is already mapped when the library is
+        # opened (same SONAME).  Opened the other way round, the library would bind to the system
+        # copy and launch kernels through a runtime that knows nothing of torch's streams and memory.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.adaspec_verify_attn_workspace_bytes.restype = C.c_size_t
@@ -87,6 +92,17 @@ def lib() -> C.CDLL:
         L.adaspec_version.restype = C.c_int
         _lib = L
     return _lib
+
+
+def hip_runtime() -> C.CDLL:
+    """The HIP runtime this process already uses (the copy torch loaded), for callers that need
+    raw HIP calls such as hipEventCreate: opening "libamdhip64.so" by name could map a second copy."""
+    lib()
+    with open("/proc/self/maps") as f:
+        paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+    if len(paths) != 1:
+        raise RuntimeError(f"expected exactly one HIP runtime in the process, found {sorted(paths)}")
+    return C.CDLL(paths.pop())
 
 
 def status_string(status: int) -> str:

@@ -159,6 +159,18 @@ def test_kv_append_and_commit_validate():
     assert L.adaspec_commit(*[None] * 10, C.byref(CommitDims(0, 3, 4, 0)), None) == 0
 
 
+def test_one_hip_runtime_whatever_the_import_order():
+    # torch ships its own HIP runtime; the library must bind to that copy even when it is the first
+    # thing a fresh process touches (checked in a child process: this one has torch loaded already)
+    import subprocess, sys
+    code = ("import paper_2503_05096_amd as p; p.lib(); "
+            "print(len({l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}))")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=root, check=True)
+    assert out.stdout.strip() == "1", out.stdout + out.stderr
+    assert pkg.binding.hip_runtime() is not None
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2503_05096_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
