@@ -32,6 +32,13 @@ extern "C" {
 typedef struct {
     double alpha_d, gamma_d, delta_d;
     double alpha_v, gamma_v, delta_v;
+    /* How the target pass counts context tokens.  0: as in Eq. 4, every verified position
+     * counts its own context (request i contributes sum_{j=1..k_i+1} (C_i + j - 1)).
+     * 1: every request's context counts ONCE, C_i + k_i + 1 tokens: the cost shape of a
+     * verification kernel that reads the cached keys and values once for all k_i + 1 positions
+     * of a request, as adaspec_verify_attn does (fit the coefficients with the same setting). */
+    int32_t verify_ctx_once;
+    int32_t reserved;
 } adaspec_time_model;
 
 /* T_sd = T_d + T_v (Eq. 1, 3, 4): `draft_steps` passes of the draft model over all B

@@ -35,6 +35,10 @@ class TimeModel:
     alpha_v: float
     gamma_v: float
     delta_v: float
+    # False: Eq. 4 as printed (every verified position counts its own context).  True: the context of
+    # a request counts once in the target pass (C_i + k_i + 1 tokens), the cost shape of a kernel
+    # that reads the cache once for all positions of a request.
+    verify_ctx_once: bool = False
 
 
 def t_fwd(alpha: float, gamma: float, delta: float, n_c: float, n_b: float) -> float:
@@ -57,8 +61,11 @@ def t_verify(m: TimeModel, C: Sequence[int], k: Sequence[int]) -> float:
     n_c = 0
     n_b = 0
     for c, ki in zip(C, k):
+        if m.verify_ctx_once:
+            n_c += int(c) + int(ki) + 1
         for j in range(1, int(ki) + 2):
-            n_c += int(c) + j - 1
+            if not m.verify_ctx_once:
+                n_c += int(c) + j - 1
             n_b += 1
     return t_fwd(m.alpha_v, m.gamma_v, m.delta_v, n_c, n_b)
 

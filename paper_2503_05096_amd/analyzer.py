@@ -72,8 +72,10 @@ def measure(B: int, ctx: int, k: int, *, iters: int, seed: int, layers: int):
     e1.record()
     torch.cuda.synchronize()
     t = e0.elapsed_time(e1) * 1e-3 / iters
+    # context tokens per position (Eq. 4 as printed) and per request (each request's cache counted once)
     n_c = float(sum(int(c) * (int(s) + 1) + int(s) * (int(s) + 1) // 2 for c, s in zip(C.tolist(), spec.tolist())))
-    return n_c, float(TQ), t
+    n_c_once = float(L.sum())
+    return n_c, n_c_once, float(TQ), t
 
 
 def main() -> int:
@@ -86,24 +88,29 @@ def main() -> int:
     grid = [(B, ctx, k) for B in (16, 64, 128) for ctx in (256, 1024, 4096) for k in (0, 3, 6)]
     rows = []
     for n, (B, ctx, k) in enumerate(grid):
-        n_c, n_b, t = measure(B, ctx, k, iters=args.iters, seed=n, layers=args.layers)
-        rows.append((B, ctx, k, n_c, n_b, t))
-        print(f"B={B:4d} ctx~{ctx:5d} k<={k}  N_c={n_c:11.0f}  N_b={n_b:5.0f}  t={t * 1e6:9.1f} us", flush=True)
+        n_c, n_c_once, n_b, t = measure(B, ctx, k, iters=args.iters, seed=n, layers=args.layers)
+        rows.append((B, ctx, k, n_c, n_c_once, n_b, t))
+        print(f"B={B:4d} ctx~{ctx:5d} k<={k}  N_c={n_c:11.0f}  N_c(once)={n_c_once:9.0f}  N_b={n_b:5.0f}  "
+              f"t={t * 1e6:9.1f} us", flush=True)
     a = np.array(rows, dtype=np.float64)
-    alpha, gamma, delta = policy.fit_time_model(a[:, 3], a[:, 4], a[:, 5])
-    pred = alpha * a[:, 3] + gamma * a[:, 4] + delta
-    ss_res, ss_tot = float(((a[:, 5] - pred) ** 2).sum()), float(((a[:, 5] - a[:, 5].mean()) ** 2).sum())
-    rec = {"layers": args.layers, "alpha_v_s_per_context_token": alpha, "gamma_v_s_per_batch_token": gamma,
-           "delta_v_s": delta, "r2": 1.0 - ss_res / ss_tot,
-           "max_rel_err": float(np.max(np.abs(pred - a[:, 5]) / a[:, 5])), "points": len(rows)}
+
+    def fit(col, once):
+        alpha, gamma, delta = policy.fit_time_model(a[:, col], a[:, 5], a[:, 6])
+        pred = alpha * a[:, col] + gamma * a[:, 5] + delta
+        ss_res, ss_tot = float(((a[:, 6] - pred) ** 2).sum()), float(((a[:, 6] - a[:, 6].mean()) ** 2).sum())
+        return {"verify_ctx_once": once, "alpha_v_s_per_context_token": alpha, "gamma_v_s_per_batch_token": gamma,
+                "delta_v_s": delta, "r2": 1.0 - ss_res / ss_tot,
+                "max_rel_err": float(np.max(np.abs(pred - a[:, 6]) / a[:, 6]))}
+
+    rec = {"layers": args.layers, "points": len(rows), "fits": [fit(3, 0), fit(4, 1)]}
     print(json.dumps(rec))
     if args.out:
         with open(args.out, "w") as f:
             f.write("# python -m paper_2503_05096_amd.analyzer --layers %d --iters %d\n" % (args.layers, args.iters))
-            f.write("# B ctx k N_c N_b t_seconds\n")
+            f.write("# B ctx k N_c(per position) N_c(once per request) N_b t_seconds\n")
             for r in rows:
-                f.write("%d %d %d %.0f %.0f %.6e\n" % r)
-            f.write(json.dumps(rec) + "\n")
+                f.write("%d %d %d %.0f %.0f %.0f %.6e\n" % r)
+            f.write(json.dumps(rec, indent=1) + "\n")
     return 0
 
 

@@ -15,6 +15,11 @@ namespace {
 
 // sum over j = 1..n of (C + j - 1): context tokens of n consecutive passes / positions
 inline double ctx_tokens(double C, double n) { return n * C + n * (n - 1.0) * 0.5; }
+// context tokens the target pass is charged for a request with k drafts
+inline double verify_ctx(const adaspec_time_model &m, double C, double k)
+{
+    return m.verify_ctx_once ? C + k + 1.0 : ctx_tokens(C, k + 1.0);
+}
 
 struct Sums {
     double sum_c = 0.0;      // sum of C_i
@@ -50,7 +55,7 @@ double adaspec_policy_estimate_time(const adaspec_time_model *m, int32_t B, cons
         const int k = spec_lens ? spec_lens[i] : draft_steps;
         if (k < 0 || k > draft_steps) return NAN;
         s.sum_c += C[i];
-        n_c += ctx_tokens(C[i], k + 1.0);
+        n_c += verify_ctx(*m, C[i], k);
         n_b += k + 1.0;
     }
     return draft_time(*m, s, draft_steps) + verify_time(*m, n_c, n_b);
@@ -86,7 +91,8 @@ int adaspec_policy_adaptive_draft(const adaspec_time_model *m, int32_t B, const 
     double nat = B;                      // bonus tokens
     double best = -1.0;
     auto time_at = [&](int st) {         // all requests verified at st drafts each
-        double n_c = (st + 1.0) * s.sum_c + B * (st + 1.0) * st * 0.5;
+        double n_c = m->verify_ctx_once ? s.sum_c + B * (st + 1.0)
+                                        : (st + 1.0) * s.sum_c + B * (st + 1.0) * st * 0.5;
         return draft_time(*m, s, st) + verify_time(*m, n_c, (st + 1.0) * B);
     };
     for (;;) {
@@ -125,7 +131,7 @@ int adaspec_policy_eliminate(const adaspec_time_model *m, int32_t B, const int32
     for (int i = 0; i < B; ++i) {
         s.sum_c += C[i];
         spec_lens_out[i] = draft_steps;
-        n_c += ctx_tokens(C[i], draft_steps + 1.0);
+        n_c += verify_ctx(*m, C[i], draft_steps);
         n_b += draft_steps + 1.0;
         nat += 1.0;
         for (int st = 0; st < draft_steps; ++st) nat += ar[(int64_t)st * B + i];
@@ -145,8 +151,10 @@ int adaspec_policy_eliminate(const adaspec_time_model *m, int32_t B, const int32
         }
         if (cand < 0) break;
         const int k = spec_lens_out[cand];
-        // dropping the last draft of `cand` removes position k + 1 (context C + k) and one batch token
-        const double nat2 = nat - lo, n_c2 = n_c - (C[cand] + (double)k), n_b2 = n_b - 1.0;
+        // dropping the last draft of `cand` removes position k + 1 (its context: C + k tokens, or the one
+        // token it added to the request's cache when contexts count once) and one batch token
+        const double nat2 = nat - lo, n_b2 = n_b - 1.0;
+        const double n_c2 = n_c - (m->verify_ctx_once ? 1.0 : C[cand] + (double)k);
         const double g = gp(nat2, n_c2, n_b2);
         if (!(g > best)) break;
         best = g; nat = nat2; n_c = n_c2; n_b = n_b2;

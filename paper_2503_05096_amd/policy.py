@@ -22,7 +22,8 @@ EXPORTS = (
 class TimeModel(C.Structure):
     """Coefficients of T = alpha * N_c + gamma * N_b + delta for the draft (d) and target (v) models."""
     _fields_ = [("alpha_d", C.c_double), ("gamma_d", C.c_double), ("delta_d", C.c_double),
-                ("alpha_v", C.c_double), ("gamma_v", C.c_double), ("delta_v", C.c_double)]
+                ("alpha_v", C.c_double), ("gamma_v", C.c_double), ("delta_v", C.c_double),
+                ("verify_ctx_once", C.c_int32), ("reserved", C.c_int32)]
 
 
 _ready = False

@@ -19,8 +19,9 @@ from paper_2503_05096_amd import policy as PP
 M = OP.TimeModel(alpha_d=2e-7, gamma_d=3e-5, delta_d=4e-3, alpha_v=9e-7, gamma_v=2e-4, delta_v=2.5e-2)
 
 
-def _lib_model(m=M):
-    return PP.TimeModel(m.alpha_d, m.gamma_d, m.delta_d, m.alpha_v, m.gamma_v, m.delta_v)
+def _lib_model(m=None):
+    m = M if m is None else m
+    return PP.TimeModel(m.alpha_d, m.gamma_d, m.delta_d, m.alpha_v, m.gamma_v, m.delta_v, int(m.verify_ctx_once), 0)
 
 
 # ------------------------------------------------------------------ oracle pins
@@ -122,6 +123,16 @@ def test_fit_recovers_exact_coefficients():
     assert math.isclose(a, 3e-7, rel_tol=1e-9) and math.isclose(g, 2e-4, rel_tol=1e-9) and math.isclose(d, 0.011, rel_tol=1e-9)
 
 
+def test_context_counted_once_variant():
+    import dataclasses
+    m1 = dataclasses.replace(M, verify_ctx_once=True)
+    C, k = [10, 200, 33], [2, 0, 1]
+    tv = M.alpha_v * ((10 + 3) + (200 + 1) + (33 + 2)) + M.gamma_v * 6 + M.delta_v
+    assert math.isclose(OP.t_verify(m1, C, k), tv, rel_tol=1e-13)
+    # with no drafts the two counts differ only by the request's own new token (it is read from the cache too)
+    assert math.isclose(OP.t_verify(m1, C, [0, 0, 0]) - OP.t_verify(M, C, [0, 0, 0]), 3 * M.alpha_v, rel_tol=1e-9)
+
+
 # ------------------------------------------------------------------ library (host C++) against the oracle
 def _random_case(rng, B, SL):
     C = rng.integers(1, 5000, B).astype(np.int32)
@@ -145,7 +156,18 @@ def test_library_time_and_goodput_match_oracle(seed):
 
 @pytest.mark.parametrize("seed", range(12))
 def test_library_drafter_and_elimination_match_oracle(seed):
+    import dataclasses
+    global M
     rng = np.random.default_rng(100 + seed)
+    M0 = M
+    M = dataclasses.replace(M0, verify_ctx_once=bool(seed & 1))
+    try:
+        _drafter_and_elimination_case(rng)
+    finally:
+        M = M0
+
+
+def _drafter_and_elimination_case(rng):
     B, SL = int(rng.integers(1, 64)), int(rng.integers(1, 9))
     C, conf = _random_case(rng, B, SL)
     prev = float(rng.uniform(0.3, 0.95))
