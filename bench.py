@@ -236,6 +236,41 @@ def main() -> int:
                            "unit": "verified query-tokens/s", "n_layers": n_layers,
                            "note": "n_layers x attention main kernel + 1 acceptance main kernel (kernel times only)"},
     }
+    # the steps either side of the hot path (not part of `value`): draft-side sampling of one draft
+    # step for the whole batch, KV append of the step's new tokens, commit of the accepted ones
+    def timed(fn, n=20):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    d_logits = dev0.target_logits[:B]
+    d_temp = torch.full((B,), 1.0, device="cuda:0")
+    d_uni = torch.rand(B, device="cuda:0")
+    d_probs = torch.empty_like(d_logits)
+    d_tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    d_conf = torch.empty(B, dtype=torch.float32, device="cuda:0")
+    t_draft = timed(lambda: pkg.draft_sample(d_logits, d_temp, d_uni, draft_probs=d_probs, draft_tokens=d_tok,
+                                             confidence=d_conf))
+    k_new = torch.randn(st.total_q, st.n_kv_heads, st.head_dim, device="cuda:0").to(dev0.q.dtype)
+    t_append = timed(lambda: pkg.kv_append(k_new, k_new, dev0.k_pages, dev0.v_pages, dev0.block_table,
+                                           dev0.ctx_lens, dev0.spec_lens, max_spec_len=kmax))
+    com, last = torch.empty(B, dtype=torch.int32, device="cuda:0"), torch.empty(B, dtype=torch.int32, device="cuda:0")
+    t_commit = timed(lambda: pkg.commit(toks, alen, dev0.spec_lens, dev0.ctx_lens, max_spec_len=kmax,
+                                        committed_lens=com, last_token=last))
+    draft_bytes = B * st.vocab * (d_logits.element_size() + d_probs.element_size())
+    rec["around_the_step"] = {
+        "draft_sample": {"rows": B, "ms": t_draft, "algorithmic_bytes": draft_bytes,
+                         "achieved_GBs": gbs(draft_bytes, t_draft), "frac": gbs(draft_bytes, t_draft) / HBM_PEAK_GBS,
+                         "note": "one draft step of the whole batch: logits row in, probability row out"},
+        "kv_append_ms": t_append, "commit_ms": t_commit,
+        "note": "timed back to back on warm caches, launch overhead included; not part of `value`"}
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(st)
     print(json.dumps(rec))

@@ -232,10 +232,51 @@ int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
                    const adaspec_commit_dims *dims, void *stream);
 
 /* ------------------------------------------------------------------------
+ * Draft-side sampling: the producer of draft_probs, draft_tokens and of the
+ * confidence scores the speculative-length policy consumes (paper Sec. 4.2,
+ * Eq. 6: a draft token's acceptance rate is modelled by the product of the
+ * confidence scores c_{i,k}; Alg. 1: every execution of the draft model
+ * returns the draft tokens and their confidences).
+ *
+ * For each of `rows` rows of draft-model logits, with T = temperature[r]:
+ *   T > 0 : q = softmax(logits / T), every entry rounded ONCE (nearest-even) to
+ *           probs_dtype and stored; token = smallest t whose inclusive prefix
+ *           sum of the ROUNDED row exceeds uniforms[r] * (sum of the rounded
+ *           row), so a token of probability zero is never drawn;
+ *   T == 0: greedy drafting: token = argmax(logits) (lowest index on ties) and
+ *           q = softmax(logits) (temperature 1), rounded and stored;
+ *   confidence[r] = q[token] as stored, widened to float.
+ * The row is written to draft_probs row out_rows[r] (row r if out_rows is
+ * NULL), so a caller can place it directly into the ragged [TD][V] layout
+ * that adaspec_accept reads.
+ *
+ * Needs V % 8 == 0, V <= 524288, row strides that are multiples of 8 elements
+ * and 16-byte aligned logits / draft_probs (ADASPEC_ERR_UNSUPPORTED or
+ * ADASPEC_ERR_ALIGN otherwise).  No workspace.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t rows;               /* R >= 0                                      */
+    int32_t vocab;              /* V                                           */
+    int32_t logits_dtype;       /* adaspec_dtype of draft_logits               */
+    int32_t probs_dtype;        /* adaspec_dtype of draft_probs                */
+    int64_t logits_row_stride;  /* elements between logits rows, >= V          */
+    int64_t probs_row_stride;   /* elements between draft_probs rows, >= V     */
+} adaspec_draft_dims;
+
+int adaspec_draft_sample(const void *draft_logits,      /* [R][V]                               */
+                         const float *temperature,      /* [R] >= 0                             */
+                         const float *uniforms,         /* [R] in [0, 1)                        */
+                         const int32_t *out_rows,       /* [R] destination rows, or NULL        */
+                         void *draft_probs,             /* [max(out_rows)+1][V], written        */
+                         int32_t *draft_tokens,         /* [R]                                  */
+                         float *confidence,             /* [R]                                  */
+                         const adaspec_draft_dims *dims, void *stream);
+
+/* ------------------------------------------------------------------------
  * Per-kernel timing for benchmarks: when both events are non-NULL, the next
  * calls record `start` (hipEvent_t) right before and `stop` right after the
  * launch of the selected kernel on the call's stream.  Pass NULLs to clear.
- * which: 0 = attention main kernel, 1 = accept main kernel.
+ * which: 0 = attention main kernel, 1 = accept main kernel, 2 = draft sampling kernel.
  * ---------------------------------------------------------------------- */
 int adaspec_set_timing_events(int which, void *start_event, void *stop_event);
 

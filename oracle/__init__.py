@@ -50,6 +50,9 @@ def _load():
                                           C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_accept.restype = C.c_int
         L.oracle_accept.argtypes = [C.c_void_p] * 9 + [C.c_int] * 4 + [C.c_int64, C.c_int64, C.c_int]
+        L.oracle_draft_sample.restype = C.c_int
+        L.oracle_draft_sample.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_void_p,
+                                          C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -150,3 +153,22 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
     if rc != 0:
         raise ValueError(f"oracle_accept rejected its inputs (code {rc})")
     return toks, alen, info
+
+
+def draft_sample(draft_logits, temperature, uniforms, *, logits_dtype: str, probs_dtype: str):
+    """Draft-side sampling of every row.  Returns (q [R][V] float64: the rounded draft-probability
+    rows, tokens [R] int32, confidence [R] float64, info [R][5] = token, confidence, Q = sum q,
+    prefix sum before the token, prefix sum including it)."""
+    L = _load()
+    lg = _c(draft_logits)
+    R, V = lg.shape
+    temp = _c(np.asarray(temperature, dtype=np.float32))
+    uni = _c(np.asarray(uniforms, dtype=np.float32))
+    q = np.zeros((R, V), np.float64)
+    tok = np.zeros(R, np.int32)
+    conf = np.zeros(R, np.float64)
+    info = np.zeros((R, 5), np.float64)
+    rc = L.oracle_draft_sample(_p(lg), _DT[logits_dtype], V, R, V, _p(temp), _p(uni), _DT[probs_dtype],
+                               _p(q), _p(tok), _p(conf), _p(info))
+    assert rc == 0
+    return q, tok, conf, info

@@ -353,6 +353,77 @@ int oracle_accept(const void *target_logits, const void *draft_probs,
     return 0;
 }
 
+/* =========================================================================
+ * Draft-side sampling (paper Eq. 6: confidence scores c_{i,k}; Alg. 1: each run
+ * of the draft model returns draft tokens and their confidences).
+ *
+ * One row of draft logits, temperature T, one uniform u:
+ *   T > 0 : p = softmax(l / T); q_v = p_v rounded once to the storage type qdt;
+ *           token = smallest t with sum_{v<=t} q_v > u * sum_v q_v (sums over the
+ *           ROUNDED values, so a zero-probability token is never drawn; if
+ *           rounding leaves no crossing, the last token with q > 0);
+ *   T == 0: token = argmax l (lowest index on ties); q = softmax(l) at T = 1, rounded;
+ *   confidence = q[token].
+ * out_q [V]: the rounded row as doubles.
+ * res[0] = token, res[1] = confidence, res[2] = Q = sum q, res[3] = prefix sum
+ * before the token, res[4] = prefix sum including it (res[3..4] NaN if T == 0).
+ * ======================================================================= */
+void oracle_draft_sample_row(const void *logits, int ldt, int V, double T, double u, int qdt,
+                             double *out_q, double *res)
+{
+    int z = 0;
+    double m = load(logits, 0, ldt);
+    for (int v = 1; v < V; ++v) {
+        double l = load(logits, v, ldt);
+        if (l > m) { m = l; z = v; }
+    }
+    const double temp = (T == 0.0) ? 1.0 : T;
+    double Z = 0.0;
+    for (int v = 0; v < V; ++v) { out_q[v] = exp((load(logits, v, ldt) - m) / temp); Z += out_q[v]; }
+    double Q = 0.0;
+    for (int v = 0; v < V; ++v) { out_q[v] = round_to_dtype(out_q[v] / Z, qdt); Q += out_q[v]; }
+    res[2] = Q; res[3] = NAN; res[4] = NAN;
+    if (T == 0.0) {
+        res[0] = (double)z; res[1] = out_q[z];
+        return;
+    }
+    const double thr = u * Q;
+    double c = 0.0, before = 0.0;
+    int cand = -1, last_pos = 0;
+    for (int v = 0; v < V; ++v) {
+        before = c;
+        c += out_q[v];
+        if (out_q[v] > 0.0) last_pos = v;
+        if (c > thr) { cand = v; break; }
+    }
+    if (cand < 0) {
+        cand = last_pos;
+        c = 0.0;
+        for (int v = 0; v < cand; ++v) c += out_q[v];
+        before = c; c += out_q[cand];
+    }
+    res[0] = (double)cand; res[1] = out_q[cand]; res[3] = before; res[4] = c;
+}
+
+/* All rows: out_q [R][V] doubles, tokens [R], conf [R] doubles, info [R][5] = res of every row. */
+int oracle_draft_sample(const void *logits, int ldt, int64_t lstride, int R, int V,
+                        const float *temperature, const float *uniforms, int qdt,
+                        double *out_q, int32_t *tokens, double *conf, double *info)
+{
+    const size_t esz = (ldt == DT_F32) ? 4 : 2;
+#pragma omp parallel for schedule(dynamic)
+    for (int r = 0; r < R; ++r) {
+        double res[5];
+        oracle_draft_sample_row((const char *)logits + (size_t)r * (size_t)lstride * esz, ldt, V,
+                                (double)temperature[r], (double)uniforms[r], qdt,
+                                out_q + (size_t)r * (size_t)V, res);
+        tokens[r] = (int32_t)res[0];
+        conf[r] = res[1];
+        if (info) memcpy(info + (size_t)r * 5, res, sizeof(res));
+    }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
     int n = 1;

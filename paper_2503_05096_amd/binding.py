@@ -20,7 +20,7 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST}
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
     "adaspec_accept_workspace_bytes", "adaspec_accept",
-    "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
+    "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit", "adaspec_draft_sample",
     "adaspec_set_timing_events",
     "adaspec_status_string", "adaspec_version",
 )
@@ -45,6 +45,11 @@ class AcceptDims(C.Structure):
 class CommitDims(C.Structure):
     _fields_ = [("batch", C.c_int32), ("max_spec_len", C.c_int32), ("out_stride", C.c_int32),
                 ("seq_stride", C.c_int32)]
+
+
+class DraftDims(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("vocab", C.c_int32), ("logits_dtype", C.c_int32),
+                ("probs_dtype", C.c_int32), ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64)]
 
 
 class AdaspecError(RuntimeError):
@@ -85,6 +90,8 @@ def lib() -> C.CDLL:
         L.adaspec_kv_append.argtypes = [vp] * 7 + [C.POINTER(AttnDims), vp]
         L.adaspec_commit.restype = C.c_int
         L.adaspec_commit.argtypes = [vp] * 10 + [C.POINTER(CommitDims), vp]
+        L.adaspec_draft_sample.restype = C.c_int
+        L.adaspec_draft_sample.argtypes = [vp] * 7 + [C.POINTER(DraftDims), vp]
         L.adaspec_set_timing_events.restype = C.c_int
         L.adaspec_set_timing_events.argtypes = [C.c_int, vp, vp]
         L.adaspec_status_string.restype = C.c_char_p
@@ -285,6 +292,33 @@ def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, *, max_spec_len: int
     if rc != 0:
         raise AdaspecError(rc, "adaspec_commit")
     return committed_lens, next_ctx_lens, last_token
+
+
+def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft_probs=None, out_rows=None,
+                 draft_tokens=None, confidence=None, stream=None):
+    """adaspec_draft_sample; returns (draft_probs, draft_tokens [R] int32, confidence [R] float32)."""
+    import torch
+    R, V = draft_logits.shape
+    dev = draft_logits.device
+    assert draft_logits.is_cuda and draft_logits.stride(1) == 1
+    assert temperature.dtype == torch.float32 and uniforms.dtype == torch.float32
+    if draft_probs is None:
+        assert out_rows is None
+        draft_probs = torch.empty((R, V), dtype=probs_dtype or draft_logits.dtype, device=dev)
+    assert draft_probs.stride(1) == 1 and draft_probs.shape[1] == V
+    if draft_tokens is None:
+        draft_tokens = torch.empty((R,), dtype=torch.int32, device=dev)
+    if confidence is None:
+        confidence = torch.empty((R,), dtype=torch.float32, device=dev)
+    dims = DraftDims(R, V, _dtype_code(draft_logits), _dtype_code(draft_probs), draft_logits.stride(0),
+                     draft_probs.stride(0))
+    rc = lib().adaspec_draft_sample(draft_logits.data_ptr(), temperature.data_ptr(), uniforms.data_ptr(),
+                                    None if out_rows is None else out_rows.data_ptr(), draft_probs.data_ptr(),
+                                    draft_tokens.data_ptr(), confidence.data_ptr(), C.byref(dims),
+                                    _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_draft_sample")
+    return draft_probs, draft_tokens, confidence
 
 
 def set_timing_events(which: int, start_event_ptr: Optional[int], stop_event_ptr: Optional[int]) -> None:

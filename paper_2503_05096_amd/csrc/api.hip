@@ -10,8 +10,8 @@
 
 namespace adaspec {
 
-static hipEvent_t g_ev_start[2] = {nullptr, nullptr};
-static hipEvent_t g_ev_stop[2] = {nullptr, nullptr};
+static hipEvent_t g_ev_start[3] = {nullptr, nullptr, nullptr};
+static hipEvent_t g_ev_stop[3] = {nullptr, nullptr, nullptr};
 
 static bool dtype_ok(int dt) { return dt == ADASPEC_F32 || dt == ADASPEC_F16 || dt == ADASPEC_BF16; }
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -253,9 +253,32 @@ int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
     return ADASPEC_OK;
 }
 
+int adaspec_draft_sample(const void *draft_logits, const float *temperature, const float *uniforms,
+                         const int32_t *out_rows, void *draft_probs, int32_t *draft_tokens,
+                         float *confidence, const adaspec_draft_dims *d, void *stream)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->rows < 0 || d->vocab <= 0) return ADASPEC_ERR_DIM;
+    if (d->logits_row_stride < d->vocab || d->probs_row_stride < d->vocab) return ADASPEC_ERR_DIM;
+    if (!dtype_ok(d->logits_dtype) || !dtype_ok(d->probs_dtype)) return ADASPEC_ERR_DTYPE;
+    if (d->rows == 0) return ADASPEC_OK;
+    if (!draft_logits || !temperature || !uniforms || !draft_probs || !draft_tokens || !confidence)
+        return ADASPEC_ERR_NULL;
+    if (!aligned16(draft_logits) || !aligned16(draft_probs)) return ADASPEC_ERR_ALIGN;
+    if (!draft_sample_supported(*d, draft_logits, draft_probs)) return ADASPEC_ERR_UNSUPPORTED;
+    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_start[2], static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
+                            confidence, *d, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_stop[2], static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
 int adaspec_set_timing_events(int which, void *start_event, void *stop_event)
 {
-    if (which < 0 || which > 1) return ADASPEC_ERR_DIM;
+    if (which < 0 || which > 2) return ADASPEC_ERR_DIM;
     g_ev_start[which] = static_cast<hipEvent_t>(start_event);
     g_ev_stop[which] = static_cast<hipEvent_t>(stop_event);
     return ADASPEC_OK;

@@ -127,7 +127,7 @@ def test_accept_rejects_null_and_small_workspace():
 
 def test_misc_entry_points_validate():
     L = pkg.lib()
-    assert L.adaspec_set_timing_events(2, None, None) == -2
+    assert L.adaspec_set_timing_events(3, None, None) == -2
     assert L.adaspec_set_timing_events(0, None, None) == 0
     assert L.adaspec_check_ragged_inputs(None, PTR, PTR, C.byref(_attn_dims()), PTR, None) == -1
     assert L.adaspec_check_ragged_inputs(PTR, PTR, PTR, C.byref(_attn_dims(batch=-1)), PTR, None) == -2
@@ -157,6 +157,24 @@ def test_kv_append_and_commit_validate():
     both = list(args); both[8] = PTR; both[9] = PTR
     assert L.adaspec_commit(*both, C.byref(c), None) == -2                            # seq_stride 0
     assert L.adaspec_commit(*[None] * 10, C.byref(CommitDims(0, 3, 4, 0)), None) == 0
+
+
+def test_draft_sample_validates():
+    from paper_2503_05096_amd.binding import DraftDims
+    L = pkg.lib()
+    ok = DraftDims(4, 1024, BF16, BF16, 1024, 1024)
+    args = [PTR, PTR, PTR, None, PTR, PTR, PTR]
+    assert L.adaspec_draft_sample(*args, None, None) == -1
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(-1, 1024, BF16, BF16, 1024, 1024)), None) == -2
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1000, 1024)), None) == -2
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, 9, BF16, 1024, 1024)), None) == -3
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1001, BF16, BF16, 1001, 1001)), None) == -6
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1028, 1024)), None) == -6
+    bad = list(args); bad[0] = None
+    assert L.adaspec_draft_sample(*bad, C.byref(ok), None) == -1
+    mis = list(args); mis[4] = PTR + 8
+    assert L.adaspec_draft_sample(*mis, C.byref(ok), None) == -4
+    assert L.adaspec_draft_sample(*[None] * 7, C.byref(DraftDims(0, 1024, BF16, BF16, 1024, 1024)), None) == 0
 
 
 def test_one_hip_runtime_whatever_the_import_order():
