@@ -188,3 +188,30 @@ def test_multi_step_decode_loop(oracle_mod, pkg):
         committed, ctx, spec = ref["committed_lens"], ref["next_ctx_lens"], nxt
         ctx_d = nctx_d
     assert seq_lens.sum() > 3 * B - 1                                   # every request emitted >= 1 token per step
+
+
+def test_append_and_commit_with_many_requests(pkg):
+    import torch
+    dev = "cuda:0"
+    rng = np.random.default_rng(15)
+    B = 1500
+    spec = rng.integers(0, 4, B).astype(np.int32)
+    ctx = (rng.integers(0, 50, B) + spec + 1).astype(np.int32)
+    st = W.make_custom_step(16, ctx_lens=ctx, spec_lens=spec, n_q_heads=2, n_kv_heads=2, head_dim=64, dtype="f16",
+                            acceptance=False)
+    shape = (st.total_q, 2, 64)
+    k_new, v_new = _new_rows(rng, shape, "f16"), _new_rows(rng, shape, "f16")
+    k_ref, v_ref = KV.kv_append(k_new, v_new, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens)
+    kp, vp = _torch_from(st.k_pages, "f16", dev), _torch_from(st.v_pages, "f16", dev)
+    _say(f"kv_append B={B} TQ={st.total_q}")
+    t = lambda a: torch.from_numpy(a).to(dev)
+    pkg.kv_append(_torch_from(k_new, "f16", dev), _torch_from(v_new, "f16", dev), kp, vp, t(st.block_table),
+                  t(st.ctx_lens), t(st.spec_lens), max_spec_len=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(kp), _host_bits(k_ref)) and np.array_equal(_bits(vp), _host_bits(v_ref))
+    alen = np.minimum(rng.integers(0, 4, B), spec).astype(np.int32)
+    toks = rng.integers(0, 1000, (B, 4)).astype(np.int32)
+    ref = KV.commit(toks, alen, spec, ctx)
+    com, _, last = pkg.commit(t(toks), t(alen), t(spec), t(ctx), max_spec_len=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(com.cpu().numpy(), ref["committed_lens"]) and np.array_equal(last.cpu().numpy(), ref["last_token"])

@@ -245,3 +245,18 @@ def test_policy_shaped_raggedness(oracle_mod, pkg):
                             logits_sigma=3.0, noise_sigma=1.5, draft_temp=1.2, name="policy-shaped")
     check_attention(st, oracle_mod, pkg)
     check_accept(st, oracle_mod, pkg)
+
+
+def test_more_than_1024_requests(oracle_mod, pkg):
+    """Batches above 1024 requests take the multi-pass form of every in-kernel scan (row -> request in the
+    acceptance kernel, the emit kernel, the attention plan)."""
+    rng = np.random.default_rng(1500)
+    B = 1500
+    spec = rng.integers(0, 3, B).astype(np.int32)
+    ctx = (rng.integers(1, 40, B) + spec + 1).astype(np.int32)
+    st = W.make_custom_step(1500, ctx_lens=ctx, spec_lens=spec, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                            dtype="bf16", vocab=1024, logits_dtype="bf16",
+                            temperature=rng.choice(np.array([0.0, 0.8, 1.0], np.float32), B), name="b1500")
+    check_attention(st, oracle_mod, pkg)
+    check_accept(st, oracle_mod, pkg)
+    check_accept(st, oracle_mod, pkg, path="vector")
