@@ -90,3 +90,10 @@ def test_algorithmic_bytes_formula():
     assert b["block_table"] == (3 + 2) * 4
     assert b["logits"] == 4 * 64 * 2 and b["probs"] == 2 * 64 * 2
     assert b["total"] == b["attn"] + b["accept"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
