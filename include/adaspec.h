@@ -261,6 +261,10 @@ typedef struct {
     int32_t probs_dtype;        /* adaspec_dtype of draft_probs                */
     int64_t logits_row_stride;  /* elements between logits rows, >= V          */
     int64_t probs_row_stride;   /* elements between draft_probs rows, >= V     */
+    int32_t path;               /* adaspec_path: FAST = register-resident kernel
+                                   (16-bit logits, V <= 131072), VECTOR = the
+                                   three-sweep kernel, AUTO = FAST when it fits  */
+    int32_t reserved;
 } adaspec_draft_dims;
 
 int adaspec_draft_sample(const void *draft_logits,      /* [R][V]                               */

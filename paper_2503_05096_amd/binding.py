@@ -49,7 +49,8 @@ class CommitDims(C.Structure):
 
 class DraftDims(C.Structure):
     _fields_ = [("rows", C.c_int32), ("vocab", C.c_int32), ("logits_dtype", C.c_int32),
-                ("probs_dtype", C.c_int32), ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64)]
+                ("probs_dtype", C.c_int32), ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64),
+                ("path", C.c_int32), ("reserved", C.c_int32)]
 
 
 class AdaspecError(RuntimeError):
@@ -295,7 +296,7 @@ def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, *, max_spec_len: int
 
 
 def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft_probs=None, out_rows=None,
-                 draft_tokens=None, confidence=None, stream=None):
+                 draft_tokens=None, confidence=None, path: str = "auto", stream=None):
     """adaspec_draft_sample; returns (draft_probs, draft_tokens [R] int32, confidence [R] float32)."""
     import torch
     R, V = draft_logits.shape
@@ -311,7 +312,7 @@ def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft
     if confidence is None:
         confidence = torch.empty((R,), dtype=torch.float32, device=dev)
     dims = DraftDims(R, V, _dtype_code(draft_logits), _dtype_code(draft_probs), draft_logits.stride(0),
-                     draft_probs.stride(0))
+                     draft_probs.stride(0), _PATHS[path], 0)
     rc = lib().adaspec_draft_sample(draft_logits.data_ptr(), temperature.data_ptr(), uniforms.data_ptr(),
                                     None if out_rows is None else out_rows.data_ptr(), draft_probs.data_ptr(),
                                     draft_tokens.data_ptr(), confidence.data_ptr(), C.byref(dims),

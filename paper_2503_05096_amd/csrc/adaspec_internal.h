@@ -96,6 +96,10 @@ bool draft_sample_supported(const adaspec_draft_dims &d, const void *logits, con
 hipError_t launch_draft_sample(const void *logits, const float *temperature, const float *uniforms,
                                const int32_t *out_rows, void *probs, int32_t *tokens, float *confidence,
                                const adaspec_draft_dims &d, hipStream_t stream);
+bool draft_fast_supported(const adaspec_draft_dims &d);
+hipError_t launch_draft_fast(const void *logits, const float *temperature, const float *uniforms,
+                             const int32_t *out_rows, void *probs, int32_t *tokens, float *confidence,
+                             const adaspec_draft_dims &d, hipStream_t stream);
 hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_pages, void *v_pages,
                             const int32_t *block_table, const int32_t *ctx_lens,
                             const int32_t *spec_lens, const adaspec_attn_dims &d, hipStream_t stream);

@@ -266,11 +266,18 @@ int adaspec_draft_sample(const void *draft_logits, const float *temperature, con
         return ADASPEC_ERR_NULL;
     if (!aligned16(draft_logits) || !aligned16(draft_probs)) return ADASPEC_ERR_ALIGN;
     if (!draft_sample_supported(*d, draft_logits, draft_probs)) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
+    const bool fast_ok = draft_fast_supported(*d);
+    if (d->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
+    const bool fast = fast_ok && d->path != ADASPEC_PATH_VECTOR;
     if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_start[2], static_cast<hipStream_t>(stream)) != hipSuccess)
         return ADASPEC_ERR_HIP;
-    if (launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
-                            confidence, *d, static_cast<hipStream_t>(stream)) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    const hipError_t e = fast
+        ? launch_draft_fast(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
+                            confidence, *d, static_cast<hipStream_t>(stream))
+        : launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
+                              confidence, *d, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_stop[2], static_cast<hipStream_t>(stream)) != hipSuccess)
         return ADASPEC_ERR_HIP;
     return ADASPEC_OK;

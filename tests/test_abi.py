@@ -162,19 +162,21 @@ def test_kv_append_and_commit_validate():
 def test_draft_sample_validates():
     from paper_2503_05096_amd.binding import DraftDims
     L = pkg.lib()
-    ok = DraftDims(4, 1024, BF16, BF16, 1024, 1024)
+    ok = DraftDims(4, 1024, BF16, BF16, 1024, 1024, 0, 0)
     args = [PTR, PTR, PTR, None, PTR, PTR, PTR]
     assert L.adaspec_draft_sample(*args, None, None) == -1
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(-1, 1024, BF16, BF16, 1024, 1024)), None) == -2
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1000, 1024)), None) == -2
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, 9, BF16, 1024, 1024)), None) == -3
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1001, BF16, BF16, 1001, 1001)), None) == -6
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1028, 1024)), None) == -6
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(-1, 1024, BF16, BF16, 1024, 1024, 0, 0)), None) == -2
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1000, 1024, 0, 0)), None) == -2
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, 9, BF16, 1024, 1024, 0, 0)), None) == -3
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1001, BF16, BF16, 1001, 1001, 0, 0)), None) == -6
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1028, 1024, 0, 0)), None) == -6
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, F32, BF16, 1024, 1024, 2, 0)), None) == -6   # fast path needs 16-bit logits
+    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1024, 1024, 5, 0)), None) == -2
     bad = list(args); bad[0] = None
     assert L.adaspec_draft_sample(*bad, C.byref(ok), None) == -1
     mis = list(args); mis[4] = PTR + 8
     assert L.adaspec_draft_sample(*mis, C.byref(ok), None) == -4
-    assert L.adaspec_draft_sample(*[None] * 7, C.byref(DraftDims(0, 1024, BF16, BF16, 1024, 1024)), None) == 0
+    assert L.adaspec_draft_sample(*[None] * 7, C.byref(DraftDims(0, 1024, BF16, BF16, 1024, 1024, 0, 0)), None) == 0
 
 
 def test_one_hip_runtime_whatever_the_import_order():

@@ -46,7 +46,7 @@ def _as_f64(t, dt):
     return a.numpy().astype(np.float64)
 
 
-def _check(logits, ldt, pdt, T, u, oracle, pkg, out_rows=None, n_prob_rows=None):
+def _check(logits, ldt, pdt, T, u, oracle, pkg, out_rows=None, n_prob_rows=None, path="auto"):
     import torch
     dev = "cuda:0"
     R, V = logits.shape
@@ -57,10 +57,10 @@ def _check(logits, ldt, pdt, T, u, oracle, pkg, out_rows=None, n_prob_rows=None)
     if out_rows is not None:
         probs = torch.zeros((n_prob_rows, V), dtype=tdt, device=dev)
         rows_d = torch.from_numpy(out_rows).to(dev)
-    _say(f"draft_sample R={R} V={V} logits={ldt} probs={pdt}")
+    _say(f"draft_sample R={R} V={V} logits={ldt} probs={pdt} path={path}")
     q_d, tok_d, conf_d = pkg.draft_sample(_torch_from(logits, ldt, dev), torch.from_numpy(T).to(dev),
                                           torch.from_numpy(u).to(dev), probs_dtype=tdt, draft_probs=probs,
-                                          out_rows=rows_d)
+                                          out_rows=rows_d, path=path)
     torch.cuda.synchronize()
     q = _as_f64(q_d, pdt)
     if out_rows is not None:
@@ -98,7 +98,11 @@ def test_draft_sample_on_config_logits(cfg, oracle_mod, pkg):
     rng = np.random.default_rng(40 + cfg)
     T = rng.choice(np.array([0.0, 0.7, 1.0, 1.2], np.float32), R).astype(np.float32)
     u = rng.random(R).astype(np.float32)
-    _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg)
+    if st.logits_dtype == "f32":
+        _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg)
+    else:
+        _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg, path="fast")
+        _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg, path="vector")
 
 
 def test_draft_sample_dtype_mixes_strides_and_row_map(oracle_mod, pkg):
@@ -110,10 +114,16 @@ def test_draft_sample_dtype_mixes_strides_and_row_map(oracle_mod, pkg):
     u[0], u[3] = 0.0, np.float32(1.0 - 2.0 ** -24)                    # the ends of the range
     for ldt, pdt in [("f32", "f32"), ("f32", "bf16"), ("bf16", "f16"), ("f16", "bf16")]:
         lg = base if ldt == "f32" else (W.f32_to_bf16_bits(base) if ldt == "bf16" else base.astype(np.float16))
-        _check(lg, ldt, pdt, T, u, oracle_mod, pkg)
+        for path in (["vector"] if ldt == "f32" else ["fast", "vector"]):
+            _check(lg, ldt, pdt, T, u, oracle_mod, pkg, path=path)
+    _check(W.f32_to_bf16_bits(base), "bf16", "f32", T, u, oracle_mod, pkg, path="fast")
     # scattered destination rows (the ragged layout the acceptance call reads)
     out_rows = np.array([3, 0, 11, 4, 5, 9, 1, 12, 7], np.int32)
-    _check(W.f32_to_bf16_bits(base), "bf16", "bf16", T, u, oracle_mod, pkg, out_rows=out_rows, n_prob_rows=13)
+    for path in ("fast", "vector"):
+        _check(W.f32_to_bf16_bits(base), "bf16", "bf16", T, u, oracle_mod, pkg, out_rows=out_rows, n_prob_rows=13, path=path)
+    # a row with no positive logit takes the exact-maximum branch of the register-resident kernel
+    neg = W.f32_to_bf16_bits(-np.abs(base[:3]) - 0.5)
+    _check(neg, "bf16", "bf16", T[:3], u[:3], oracle_mod, pkg, path="fast")
 
 
 def test_draft_sample_small_vocab_and_planted_ties(oracle_mod, pkg):
