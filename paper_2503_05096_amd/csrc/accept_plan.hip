@@ -83,12 +83,30 @@ __global__ __launch_bounds__(kPlanThreads) void accept_emit_kernel(
         const int r0 = pre + inc - n;
         if (i < B && r0 + n <= total_q) {
             const int d0 = r0 - i;
-            int a = k;
-            for (int j = 0; j < k; ++j)
-                if (row_flag[r0 + j] == 0) { a = j; break; }
             int32_t *o = out_tokens + (int64_t)i * out_stride;
-            for (int j = 0; j < a; ++j) o[j] = draft_tokens[d0 + j];
-            o[a] = row_cand[r0 + a];
+            // flags and draft tokens of the request are requested eight at a time BEFORE any of them is
+            // looked at (a loop that stops at the first rejection would pay one memory round trip per draft);
+            // the drafts are copied provisionally and everything from the stop position on is overwritten
+            int a = k;
+            int cand = row_cand[r0 + k];          // the bonus row's token, replaced below if a draft is rejected
+            for (int j0 = 0; j0 < k; j0 += 8) {
+                int f[8], t[8], c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool in = j0 + u < k;
+                    f[u] = in ? row_flag[r0 + j0 + u] : 1;
+                    t[u] = in ? draft_tokens[d0 + j0 + u] : -1;
+                    c[u] = in ? row_cand[r0 + j0 + u] : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (j0 + u < k) {
+                        if (a == k && f[u] == 0) { a = j0 + u; cand = c[u]; }
+                        o[j0 + u] = t[u];
+                    }
+                }
+            }
+            o[a] = cand;
             for (int j = a + 1; j < out_stride; ++j) o[j] = -1;
             out_accept_len[i] = a;
         }

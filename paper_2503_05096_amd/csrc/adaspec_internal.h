@@ -27,6 +27,7 @@ struct AttnPlan {
     size_t off_item_req;    // int32[max_items]
     size_t off_item_order;  // int32[max_items]: items sorted by decreasing length (schedule order)
     size_t off_unit_meta;   // int32[max_items][8] in schedule order: request, split, n_splits, L, n, cu_q, item, 0
+    size_t off_row_rec;     // int32[TQ][4] per query row: request, n_splits, first split, row base (j * G)
     size_t off_part_ml;     // float[max_items][Hkv][max_rows][2]  (m in log2 units, l)
     size_t off_part_o;      // float[max_items][Hkv][max_rows][d]
     size_t total_bytes;

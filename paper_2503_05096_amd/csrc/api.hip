@@ -68,6 +68,7 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
     p.off_item_req = off;   off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
     p.off_item_order = off; off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
     p.off_unit_meta = off;  off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 32, 256);
+    p.off_row_rec = off;    off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 16, 256);
     p.off_part_ml = off;
     off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * 2 * sizeof(float), 256);
     p.off_part_o = off;
