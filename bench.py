@@ -244,10 +244,40 @@ def main() -> int:
                      "warm_cache_ms_per_step": ms_warm,
                      "device_copy_GBs": copy_gbs,
                      "frac_of_device_copy": gbs(nbytes["total"], ms_step) / copy_gbs},
-        "model_weighted": {"value": st.total_q / ((n_layers * attn_ms + acc_ms) * 1e-3),
-                           "unit": "verified query-tokens/s", "n_layers": n_layers,
-                           "note": "n_layers x attention main kernel + 1 acceptance main kernel (kernel times only)"},
     }
+    # a whole target pass: n_layers attention layers (each with its own K/V pages and queries, the ragged
+    # metadata built once and reused) and one acceptance
+    g = torch.Generator(device="cuda:0").manual_seed(1)
+    lay_q = [torch.randn(dev0.q.shape, generator=g, device="cuda:0").to(dev0.q.dtype) for _ in range(n_layers)]
+    lay_k = [torch.randn(dev0.k_pages.shape, generator=g, device="cuda:0").to(dev0.q.dtype) for _ in range(n_layers)]
+    lay_v = [torch.randn(dev0.k_pages.shape, generator=g, device="cuda:0").to(dev0.q.dtype) for _ in range(n_layers)]
+
+    def model_pass():
+        pkg.verify_attn(lay_q[0], lay_k[0], lay_v[0], dev0.block_table, dev0.ctx_lens, dev0.spec_lens,
+                        max_spec_len=kmax, path=args.path, plan="build", workspace=ws_attn, stream=stream)
+        for l in range(n_layers):
+            pkg.verify_attn(lay_q[l], lay_k[l], lay_v[l], dev0.block_table, dev0.ctx_lens, dev0.spec_lens, out,
+                            max_spec_len=kmax, path=args.path, plan="reuse", workspace=ws_attn, stream=stream)
+        pkg.accept(dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.uniforms, dev0.spec_lens,
+                   dev0.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
+                   path=args.path, workspace=ws_acc, stream=stream)
+
+    with torch.cuda.stream(stream):
+        for _ in range(2):
+            model_pass()
+        torch.cuda.synchronize()
+        tp0 = time.perf_counter()
+        n_pass = 10
+        for _ in range(n_pass):
+            model_pass()
+        torch.cuda.synchronize()
+        ms_pass = (time.perf_counter() - tp0) * 1e3 / n_pass
+    del lay_q, lay_k, lay_v
+    rec["model_weighted"] = {"value": st.total_q / (ms_pass * 1e-3), "unit": "verified query-tokens/s",
+                             "n_layers": n_layers, "ms_per_pass": ms_pass,
+                             "note": "MEASURED: one metadata build, n_layers attention calls that reuse it (each layer "
+                                     "its own K/V pages and queries, whole calls incl. split-KV combine), one acceptance"}
+
     # the steps either side of the hot path (not part of `value`): draft-side sampling of one draft
     # step for the whole batch, KV append of the step's new tokens, commit of the accepted ones
     def timed(fn, n=20):

@@ -82,7 +82,20 @@ typedef struct {
                                    (the fp32 accumulator before the final rounding)     */
     int32_t path;               /* adaspec_path                                         */
     float   scale;              /* softmax scale; 0 means 1/sqrt(head_dim)              */
+    int32_t plan_mode;          /* adaspec_plan_mode (below); 0 for a self-contained call */
 } adaspec_attn_dims;
+
+/* The ragged metadata of a verification pass (row offsets, KV-split work list, schedule)
+ * depends only on ctx_lens and spec_lens, and every attention layer of the target model sees
+ * the same ones (paper Sec. 4.1: ONE target pass over all SL+1 positions).  A caller that runs
+ * many layers can therefore build it once:
+ *   ADASPEC_PLAN_BUILD_AND_RUN  build the metadata in the workspace, then run (default);
+ *   ADASPEC_PLAN_BUILD_ONLY     build it and return; q, k_pages, v_pages, out may be NULL;
+ *   ADASPEC_PLAN_REUSE          run with the metadata a previous call left in THIS workspace:
+ *                               same dims (except plan_mode and out_dtype), same block_table,
+ *                               ctx_lens and spec_lens contents, workspace not used by
+ *                               anything else in between.  Violations are undefined behaviour. */
+typedef enum { ADASPEC_PLAN_BUILD_AND_RUN = 0, ADASPEC_PLAN_BUILD_ONLY = 1, ADASPEC_PLAN_REUSE = 2 } adaspec_plan_mode;
 
 /* Device scratch needed by adaspec_verify_attn for these dims (0 on bad dims). */
 size_t adaspec_verify_attn_workspace_bytes(const adaspec_attn_dims *dims);

@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libadaspec.so")
 
 F32, F16, BF16 = 0, 1, 2
 PATH_AUTO, PATH_VECTOR, PATH_FAST = 0, 1, 2
+PLAN_BUILD_AND_RUN, PLAN_BUILD_ONLY, PLAN_REUSE = 0, 1, 2
+_PLAN = {"run": PLAN_BUILD_AND_RUN, "build": PLAN_BUILD_ONLY, "reuse": PLAN_REUSE}
 _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST}
 
 EXPORTS = (
@@ -31,7 +33,7 @@ class AttnDims(C.Structure):
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_size", C.c_int32), ("num_pages", C.c_int32), ("max_pages_per_req", C.c_int32),
                 ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("path", C.c_int32),
-                ("scale", C.c_float)]
+                ("scale", C.c_float), ("plan_mode", C.c_int32)]
 
 
 class AcceptDims(C.Structure):
@@ -156,27 +158,30 @@ def _workspace(nbytes: int, device, workspace):
 
 
 def attn_dims(q, k_pages, block_table, *, max_spec_len: int, scale: float = 0.0,
-              out_dtype: Optional[int] = None, path: str = "auto") -> AttnDims:
+              out_dtype: Optional[int] = None, path: str = "auto", plan: str = "run") -> AttnDims:
     dt = _dtype_code(q)
     TQ, Hq, d = q.shape
     num_pages, Hkv, P, _ = k_pages.shape
     B, max_pages = block_table.shape
     return AttnDims(B, TQ, int(max_spec_len), Hq, Hkv, d, P, num_pages, max_pages, dt,
-                    dt if out_dtype is None else int(out_dtype), _PATHS[path], float(scale))
+                    dt if out_dtype is None else int(out_dtype), _PATHS[path], float(scale), _PLAN[plan])
 
 
 def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None, *,
                 max_spec_len: int, scale: float = 0.0, out_dtype: Optional[int] = None,
-                path: str = "auto", workspace=None, stream=None):
-    """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d]."""
+                path: str = "auto", plan: str = "run", workspace=None, stream=None):
+    """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d].
+
+    plan: "run" (build the ragged metadata, then run), "build" (metadata only; returns None) or
+    "reuse" (run with the metadata a previous call left in the same workspace)."""
     import torch
     dims = attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
-                     out_dtype=out_dtype, path=path)
+                     out_dtype=out_dtype, path=path, plan=plan)
     for t in (q, k_pages, v_pages, block_table, ctx_lens, spec_lens):
         assert t.is_cuda and t.is_contiguous()
     assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32 and spec_lens.dtype == torch.int32
     assert v_pages.shape == k_pages.shape and v_pages.dtype == k_pages.dtype == q.dtype
-    if out is None:
+    if out is None and plan != "build":
         out = torch.empty(q.shape, dtype=_torch_dtype(dims.out_dtype), device=q.device)
     L = lib()
     need = L.adaspec_verify_attn_workspace_bytes(C.byref(dims))
@@ -186,7 +191,7 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     ws = _workspace(need, q.device, workspace)
     rc = L.adaspec_verify_attn(q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
                                block_table.data_ptr(), ctx_lens.data_ptr(), spec_lens.data_ptr(),
-                               out.data_ptr(), C.byref(dims), ws.data_ptr(), ws.numel(),
+                               None if out is None else out.data_ptr(), C.byref(dims), ws.data_ptr(), ws.numel(),
                                _stream_ptr(stream))
     if rc != 0:
         raise AdaspecError(rc, "adaspec_verify_attn")

@@ -31,6 +31,7 @@ static int validate_attn_dims(const adaspec_attn_dims *d)
     if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
     if (!(d->scale >= 0.0f) || isinf(d->scale)) return ADASPEC_ERR_DIM;
     if (d->path == ADASPEC_PATH_FAST && !attn_fast_path_supported(*d)) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->plan_mode < ADASPEC_PLAN_BUILD_AND_RUN || d->plan_mode > ADASPEC_PLAN_REUSE) return ADASPEC_ERR_DIM;
     return ADASPEC_OK;
 }
 
@@ -125,10 +126,11 @@ int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
     int rc = validate_attn_dims(dims);
     if (rc != ADASPEC_OK) return rc;
     if (dims->batch == 0) return ADASPEC_OK;
-    if (!q || !k_pages || !v_pages || !block_table || !ctx_lens || !spec_lens || !out || !workspace)
-        return ADASPEC_ERR_NULL;
-    if (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out) ||
-        (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    const bool plan_only = dims->plan_mode == ADASPEC_PLAN_BUILD_ONLY;
+    if (!block_table || !ctx_lens || !spec_lens || !workspace) return ADASPEC_ERR_NULL;
+    if (!plan_only && (!q || !k_pages || !v_pages || !out)) return ADASPEC_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
+    if (!plan_only && (!aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(out)))
         return ADASPEC_ERR_ALIGN;
     AttnArgs a;
     const bool fast = attn_use_fast(*dims);
@@ -141,7 +143,8 @@ int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
     const float scale = dims->scale > 0.0f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
     a.scale_log2 = scale * 1.4426950408889634f;
 
-    if (launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (dims->plan_mode != ADASPEC_PLAN_REUSE && launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (plan_only) return ADASPEC_OK;
     if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_start[0], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     hipError_t e = fast ? launch_attn_mfma(a) : launch_attn_vector(a);

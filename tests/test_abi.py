@@ -86,6 +86,16 @@ def test_attn_rejects_null_misaligned_and_small_workspace():
     assert pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(_attn_dims(out_dtype=F32))) > 0
 
 
+def test_attn_plan_mode_is_validated():
+    assert _call_attn(_attn_dims(plan_mode=3)) == -2
+    assert _call_attn(_attn_dims(plan_mode=-1)) == -2
+    # metadata-only calls do not need the tensors, but they do need the metadata inputs and a workspace
+    L = pkg.lib()
+    d = _attn_dims(plan_mode=1)
+    assert L.adaspec_verify_attn(None, None, None, None, PTR, PTR, None, C.byref(d), PTR, 1 << 30, None) == -1
+    assert L.adaspec_verify_attn(None, None, None, PTR, PTR, PTR, None, C.byref(d), PTR, 16, None) == -5
+
+
 def test_attn_workspace_grows_with_the_problem():
     f = lambda **kw: pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(_attn_dims(**kw)))
     assert f(batch=4, total_q=10) > f()

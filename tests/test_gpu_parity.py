@@ -260,3 +260,26 @@ def test_more_than_1024_requests(oracle_mod, pkg):
     check_attention(st, oracle_mod, pkg)
     check_accept(st, oracle_mod, pkg)
     check_accept(st, oracle_mod, pkg, path="vector")
+
+
+def test_attention_plan_reuse_across_layers(pkg):
+    """The ragged metadata is built once and reused by the attention calls of further layers (other Q, K, V,
+    same block table and lengths): every layer must equal a self-contained call bit for bit."""
+    import torch
+    st = W.make_verify_step(3, acceptance=False, poison=False, batch=24)
+    dev = to_device(st, acceptance=False)
+    kw = dict(max_spec_len=st.max_spec_len)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    ws2 = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    _say(f"attn plan reuse {st.name} B={st.batch}")
+    assert pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                           plan="build", workspace=ws, **kw) is None
+    g = torch.Generator(device="cuda:0").manual_seed(3)
+    for layer in range(3):
+        q = torch.randn(dev.q.shape, generator=g, device="cuda:0").to(dev.q.dtype)
+        perm = torch.randperm(dev.k_pages.shape[0], generator=g, device="cuda:0")
+        kp, vp = dev.v_pages[perm].contiguous(), dev.k_pages[perm].contiguous()      # any other cache contents
+        a = pkg.verify_attn(q, kp, vp, dev.block_table, dev.ctx_lens, dev.spec_lens, plan="reuse", workspace=ws, **kw)
+        b = pkg.verify_attn(q, kp, vp, dev.block_table, dev.ctx_lens, dev.spec_lens, workspace=ws2, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"layer {layer}"
