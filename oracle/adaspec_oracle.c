@@ -433,3 +433,14 @@ int oracle_num_threads(void)
 #endif
     return n;
 }
+
+/* Limits the OpenMP team of later calls (n >= 1); used to time the single-thread baseline. */
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
