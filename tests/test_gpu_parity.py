@@ -283,3 +283,48 @@ def test_attention_plan_reuse_across_layers(pkg):
         b = pkg.verify_attn(q, kp, vp, dev.block_table, dev.ctx_lens, dev.spec_lens, workspace=ws2, **kw)
         torch.cuda.synchronize()
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"layer {layer}"
+
+
+def test_step_replayed_from_a_hip_graph(pkg):
+    """The two calls of a step captured into one HIP graph (the library launches kernels only: no
+    allocation, no memset, no synchronisation) and replayed with new inputs in the same buffers; every
+    replay must equal the eager result bit for bit, with eager work and synchronisations in between."""
+    import torch
+    steps = [W.make_custom_step(900 + s, ctx_lens=[300, 77, 2500, 40, 1200, 640], spec_lens=[3, 0, 5, 2, 4, 1],
+                                n_q_heads=16, n_kv_heads=4, head_dim=128, dtype="bf16", vocab=8192,
+                                logits_dtype="bf16", temperature=[0.8, 1.0, 0.0, 0.7, 1.0, 0.9], poison=False)
+             for s in range(3)]
+    devs = [to_device(st) for st in steps]
+    st0 = steps[0]
+    kmax = st0.max_spec_len
+    buf = to_device(st0)                                       # static buffers the graph reads
+    names = ("q", "k_pages", "v_pages", "block_table", "target_logits", "draft_probs", "draft_tokens", "uniforms")
+    out = torch.empty_like(buf.q)
+    toks = torch.empty((st0.batch, kmax + 1), dtype=torch.int32, device="cuda:0")
+    alen = torch.empty((st0.batch,), dtype=torch.int32, device="cuda:0")
+    ws_a = torch.empty(32 << 20, dtype=torch.uint8, device="cuda:0")
+    ws_b = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+
+    def run(d, o, t, a, stream=None):
+        pkg.verify_attn(d.q, d.k_pages, d.v_pages, d.block_table, d.ctx_lens, d.spec_lens, o, max_spec_len=kmax,
+                        workspace=ws_a, stream=stream)
+        pkg.accept(d.target_logits, d.draft_probs, d.draft_tokens, d.uniforms, d.spec_lens, d.temperature,
+                   max_spec_len=kmax, out_tokens=t, out_accept_len=a, workspace=ws_b, stream=stream)
+
+    run(buf, out, toks, alen)                                  # warm-up outside the capture (one-time set-up)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    _say("capturing attention + acceptance into a HIP graph")
+    with torch.cuda.graph(g):
+        run(buf, out, toks, alen)                              # current stream = the capture stream
+    for rep in range(2):
+        for s, d in enumerate(devs):
+            ref_o, ref_t, ref_a = torch.empty_like(out), torch.empty_like(toks), torch.empty_like(alen)
+            run(d, ref_o, ref_t, ref_a)                        # eager, own buffers
+            torch.cuda.synchronize()
+            for n in names:
+                getattr(buf, n).copy_(getattr(d, n))
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), ref_o.view(torch.int16)), (rep, s)
+            assert torch.equal(toks, ref_t) and torch.equal(alen, ref_a), (rep, s)
