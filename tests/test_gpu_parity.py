@@ -135,6 +135,8 @@ EDGE_SHAPES = [
     ([257, 511, 513], [1, 0, 8], 16, 2, 64, "bf16"),  # GQA 8, 72 query rows, d = 64
     ([100, 200], [2, 1], 6, 3, 80, "f16"),            # head_dim the matrix-core path does not take
     ([2100], [5], 64, 8, 128, "bf16"),                # one long request: many splits, 48 rows
+    ([700, 90], [10, 7], 64, 8, 128, "f16"),          # 88 query rows per kv head: two row groups of 48
+    ([4097, 4096, 4095], [0, 1, 2], 8, 1, 128, "bf16"),   # just around a split boundary, one kv head
 ]
 
 
@@ -183,6 +185,8 @@ ACCEPT_EDGES = [
     ([1, 2, 3, 4], 4104, "f16", [0.0, 0.3, 1.0, 1.5]),  # fp16 logits, mixed temperatures
     ([6], 131072, "bf16", 1.0),                       # largest vocabulary of the register-resident path
     ([2], 131080, "bf16", 1.0),                       # just beyond it
+    ([2, 1, 0], 16, "bf16", [1.0, 0.0, 0.6]),          # two 16-byte chunks per row on the register-resident path
+    ([12, 9, 0, 17], 4096, "bf16", [1.0, 0.0, 0.9, 0.8]),   # more than 8 drafts per request (emit works 8 at a time)
 ]
 
 
