@@ -10,7 +10,7 @@ N_b = number of verified positions (Eq. 4).  The step timed is one attention lay
 acceptance, as in bench.py; `--layers n` weights the attention call n times (a whole model has n
 attention layers per acceptance).  The fit itself is done by adaspec_policy_fit_time_model.
 
-    python -m paper_2503_05096_amd.analyzer [--layers 32] [--out gpurun_out/time_model.txt]
+    python -m paper_2503_05096_amd.analyzer [--layers 32] [--out time_model.txt]
 
 Inputs are random device tensors of the Llama-3-8B shape (32 q heads, 8 kv heads, d = 128,
 V = 128256, bf16): the kernels' running time does not depend on the values.
