@@ -332,3 +332,24 @@ def test_step_replayed_from_a_hip_graph(pkg):
             torch.cuda.synchronize()
             assert torch.equal(out.view(torch.int16), ref_o.view(torch.int16)), (rep, s)
             assert torch.equal(toks, ref_t) and torch.equal(alen, ref_a), (rep, s)
+
+
+@pytest.mark.parametrize("path", ["fast", "vector"])
+def test_accept_with_padded_row_strides(path, oracle_mod, pkg):
+    """Logits and draft-probability rows that sit in wider buffers (row stride > V)."""
+    import torch
+    st = W.make_custom_step(77, ctx_lens=[64] * 5, spec_lens=[3, 0, 2, 5, 1], vocab=5000, logits_dtype="bf16",
+                            temperature=[1.0, 0.7, 0.0, 0.9, 1.2], attention=False, logits_sigma=3.0,
+                            noise_sigma=1.5, draft_temp=1.2, name="padded")
+    dev = to_device(st, attention=False)
+    V = st.vocab
+    wide_l = torch.full((st.total_q, V + 64), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    wide_p = torch.full((st.total_draft, V + 8), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    wide_l[:, :V] = dev.target_logits
+    wide_p[:, :V] = dev.draft_probs
+    _say(f"accept padded strides path={path}")
+    toks, alen = pkg.accept(wide_l[:, :V], wide_p[:, :V], dev.draft_tokens, dev.uniforms, dev.spec_lens,
+                            dev.temperature, max_spec_len=st.max_spec_len, path=path)
+    torch.cuda.synchronize()
+    rep = compare_accept(st, toks.cpu().numpy(), alen.cpu().numpy(), oracle_mod)
+    assert rep["hard_mismatches"] == 0 and rep["exact"] + rep["ratio_near_ties"] + rep["cdf_near_ties"] == st.batch, rep
