@@ -93,7 +93,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4g", "cfg5"])
-    ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast"])
+    ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast", "stream"],
+                    help="kernel family; 'stream' selects the streaming acceptance kernel (attention stays on auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=3,
                     help="independent device copies of the inputs, used in rotation so that no step finds its "
@@ -124,6 +125,7 @@ def main() -> int:
     from tests.harness import to_device
 
     cfg = int(args.workload[3])
+    attn_path = "auto" if args.path == "stream" else args.path
     st = W.make_verify_step(cfg, greedy=args.workload.endswith("g"), poison=False)
     nbytes = W.algorithmic_bytes(st)
     torch.cuda.set_device(0)
@@ -147,7 +149,7 @@ def main() -> int:
     toks = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
     alen = torch.empty((B,), dtype=torch.int32, device="cuda:0")
     # separate workspaces so the two calls never alias
-    a_dims = pkg.binding.attn_dims(dev.q, dev.k_pages, dev.block_table, max_spec_len=kmax, path=args.path)
+    a_dims = pkg.binding.attn_dims(dev.q, dev.k_pages, dev.block_table, max_spec_len=kmax, path=attn_path)
     ws_attn = torch.empty(max(pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(a_dims)), 256),
                           dtype=torch.uint8, device="cuda:0")
     ws_acc = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
@@ -155,7 +157,7 @@ def main() -> int:
     def step(k=0):
         dv = devs[k % ncopies]
         pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens,
-                        out, max_spec_len=kmax, path=args.path, workspace=ws_attn, stream=stream)
+                        out, max_spec_len=kmax, path=attn_path, workspace=ws_attn, stream=stream)
         pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
                    dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
                    path=args.path, workspace=ws_acc, stream=stream)
@@ -204,7 +206,7 @@ def main() -> int:
         with torch.cuda.graph(gph, stream=stream):
             dv = devs[c]
             pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens, out,
-                            max_spec_len=kmax, path=args.path, workspace=ws_attn)
+                            max_spec_len=kmax, path=attn_path, workspace=ws_attn)
             pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
                        dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
                        path=args.path, workspace=ws_acc)
@@ -300,10 +302,10 @@ def main() -> int:
 
     def model_pass():
         pkg.verify_attn(lay_q[0], lay_k[0], lay_v[0], dev0.block_table, dev0.ctx_lens, dev0.spec_lens,
-                        max_spec_len=kmax, path=args.path, plan="build", workspace=ws_attn, stream=stream)
+                        max_spec_len=kmax, path=attn_path, plan="build", workspace=ws_attn, stream=stream)
         for l in range(n_layers):
             pkg.verify_attn(lay_q[l], lay_k[l], lay_v[l], dev0.block_table, dev0.ctx_lens, dev0.spec_lens, out,
-                            max_spec_len=kmax, path=args.path, plan="reuse", workspace=ws_attn, stream=stream)
+                            max_spec_len=kmax, path=attn_path, plan="reuse", workspace=ws_attn, stream=stream)
         pkg.accept(dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.uniforms, dev0.spec_lens,
                    dev0.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
                    path=args.path, workspace=ws_acc, stream=stream)

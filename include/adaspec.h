@@ -54,7 +54,12 @@ typedef enum { ADASPEC_F32 = 0, ADASPEC_F16 = 1, ADASPEC_BF16 = 2 } adaspec_dtyp
  * matrix-core (attention) / register-resident (accept) kernel when the shape
  * allows and the portable vector kernel otherwise; the other two values force
  * one of them (ADASPEC_ERR_UNSUPPORTED if the shape does not fit it). */
-typedef enum { ADASPEC_PATH_AUTO = 0, ADASPEC_PATH_VECTOR = 1, ADASPEC_PATH_FAST = 2 } adaspec_path;
+typedef enum {
+    ADASPEC_PATH_AUTO = 0, ADASPEC_PATH_VECTOR = 1, ADASPEC_PATH_FAST = 2,
+    ADASPEC_PATH_STREAM = 3   /* adaspec_accept only: the streaming 16-bit kernel (V up to 524288), which AUTO
+                                 picks for vocabularies too large for the register-resident kernel and for
+                                 batches with more logits rows than the device has compute units */
+} adaspec_path;
 
 /* ------------------------------------------------------------------------
  * Verification attention (paper Sec. 2.2: the target scores all SL+1 positions
@@ -168,8 +173,10 @@ size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims);
  * out_accept_len[B] int32: a_i in [0, k_i]; request i emitted a_i + 1 tokens
  * Rows after a request's first rejection are still evaluated (the rows are independent;
  * the sequential rule is applied to the per-row results afterwards).
- * The register-resident path needs 16-bit logits/probs, V % 8 == 0, V <= 131072, strides % 8 == 0
- * and 16-byte aligned base pointers; anything else runs on the vector path.
+ * The register-resident path needs 16-bit logits/probs of one type, V % 8 == 0, V <= 131072,
+ * strides % 8 == 0 and 16-byte aligned base pointers; the streaming path takes the same up to
+ * V <= 524288 (it reads the logits row twice, the second time from the caches); anything else runs
+ * on the vector path.
  */
 int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const int32_t *draft_tokens, const float *uniforms,

@@ -17,7 +17,8 @@ F32, F16, BF16 = 0, 1, 2
 PATH_AUTO, PATH_VECTOR, PATH_FAST = 0, 1, 2
 PLAN_BUILD_AND_RUN, PLAN_BUILD_ONLY, PLAN_REUSE = 0, 1, 2
 _PLAN = {"run": PLAN_BUILD_AND_RUN, "build": PLAN_BUILD_ONLY, "reuse": PLAN_REUSE}
-_PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST}
+PATH_STREAM = 3
+_PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream": PATH_STREAM}
 
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",

@@ -13,6 +13,21 @@ namespace adaspec {
 static hipEvent_t g_ev_start[3] = {nullptr, nullptr, nullptr};
 static hipEvent_t g_ev_stop[3] = {nullptr, nullptr, nullptr};
 
+// compute units of the current device (asked once; 256 if the runtime cannot tell)
+static int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
 static bool dtype_ok(int dt) { return dt == ADASPEC_F32 || dt == ADASPEC_F16 || dt == ADASPEC_BF16; }
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -88,7 +103,7 @@ static int validate_accept_dims(const adaspec_accept_dims *d)
     if (!dtype_ok(d->logits_dtype) || !dtype_ok(d->probs_dtype)) return ADASPEC_ERR_DTYPE;
     if (d->logits_row_stride < d->vocab || d->probs_row_stride < d->vocab) return ADASPEC_ERR_DIM;
     if (d->out_stride < d->max_spec_len + 1) return ADASPEC_ERR_DIM;
-    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_STREAM) return ADASPEC_ERR_DIM;
     return ADASPEC_OK;
 }
 
@@ -177,8 +192,16 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     if (dims->total_draft > 0 && (!draft_probs || !draft_tokens)) return ADASPEC_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
     const bool fast_ok = accept_fast_path_supported(*dims, target_logits, draft_probs);
+    const bool stream_ok = accept_stream_path_supported(*dims, target_logits, draft_probs);
     if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
-    const bool fast = fast_ok && dims->path != ADASPEC_PATH_VECTOR;
+    if (dims->path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
+    // AUTO: the register-resident kernel holds one row per compute unit and never re-reads it, which wins
+    // while every row has a compute unit to itself; with more rows than compute units the streaming kernel
+    // (two rows per compute unit, half of each row re-read from the caches) overlaps the rows' phases and
+    // wins (measured on MI355X: 510 rows of V = 128256: 60 vs 66 us; 237 rows: 43 vs 37 us).
+    bool fast = fast_ok && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_FAST);
+    if (fast && dims->path == ADASPEC_PATH_AUTO && stream_ok && dims->total_q > compute_units()) fast = false;
+    const bool streaming = !fast && stream_ok && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_STREAM);
     AcceptArgs a;
     a.plan = make_accept_plan(*dims);
     if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;
@@ -189,10 +212,10 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     a.stream = static_cast<hipStream_t>(stream);
 
     // the register-resident kernel finds each row's request itself; only the vector kernel needs the plan
-    if (!fast && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (!fast && !streaming && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
-    hipError_t e = fast ? launch_accept_fast(a) : launch_accept_vector(a);
+    hipError_t e = fast ? launch_accept_fast(a) : (streaming ? launch_accept_stream(a) : launch_accept_vector(a));
     if (e != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;

@@ -107,6 +107,33 @@ def test_config_attention_vector_path(cfg, oracle_mod, pkg):
     check_attention(st, oracle_mod, pkg, path="vector")
 
 
+@pytest.mark.parametrize("cfg", [2, 3, 5])
+def test_config_accept_stream_path(cfg, oracle_mod, pkg):
+    st = W.make_verify_step(cfg, attention=False)
+    check_accept(st, oracle_mod, pkg, path="stream")
+
+
+STREAM_EDGES = [
+    # spec_lens, vocab, dtype, temperatures
+    ([3, 0, 2], 151936, "bf16", [0.8, 1.0, 0.0]),     # beyond the register-resident kernel: AUTO picks the streaming one
+    ([1, 4], 262144, "f16", [1.0, 0.6]),
+    ([2], 524288, "bf16", 1.0),                       # its largest vocabulary
+    ([2, 1], 8, "bf16", [1.0, 0.0]),                  # a single chunk
+    ([5, 0], 8200, "f16", [0.0, 0.9]),                # one chunk into the second step
+]
+
+
+@pytest.mark.parametrize("shape", STREAM_EDGES, ids=lambda s: f"k{s[0]}-V{s[1]}-{s[2]}")
+def test_accept_stream_edge_shapes(shape, oracle_mod, pkg):
+    spec, V, dt, T = shape
+    st = W.make_custom_step(8765, ctx_lens=[64] * len(spec), spec_lens=spec, vocab=V, logits_dtype=dt,
+                            temperature=T, attention=False, logits_sigma=3.0, noise_sigma=1.5,
+                            draft_temp=1.2, name=f"stream-{dt}")
+    check_accept(st, oracle_mod, pkg, path="stream")
+    if V > 131072:
+        check_accept(st, oracle_mod, pkg)              # AUTO must not fall back to the slow vector kernel silently
+
+
 @pytest.mark.parametrize("cfg", [3, 5])
 def test_config_accept_vector_path(cfg, oracle_mod, pkg):
     st = W.make_verify_step(cfg, attention=False, batch=24)
@@ -212,6 +239,21 @@ def test_accept_p_equals_q_accepts_everything(oracle_mod, pkg):
     st.uniforms[::2, 0] = np.float32(1.0 - 2.0 ** -24)
     rep = check_accept(st, oracle_mod, pkg)
     assert rep["oracle_mean_accept_len"] == k and rep["exact"] + rep["cdf_near_ties"] == B
+
+
+def test_accept_stream_p_equals_q_draws_from_target(oracle_mod, pkg):
+    """R == 0 on a rejected row (p == q exactly, u0 just below 1 forces the comparison u0 < 1 to hold...):
+    the kernel must fall back to drawing from p; with exact equality every draft is accepted."""
+    V, B, k = 4096, 8, 3
+    rng = np.random.default_rng(6)
+    st = W.make_custom_step(98, ctx_lens=[64] * B, spec_lens=[k] * B, vocab=V, logits_dtype="bf16",
+                            temperature=1.0, attention=False)
+    st.target_logits[:] = W.f32_to_bf16_bits(np.full(1, 0.25, np.float32))[0]      # p = 1/V exactly
+    st.draft_probs[:] = W.f32_to_bf16_bits(np.full(1, 1.0 / V, np.float32))[0]
+    st.draft_tokens[:] = rng.integers(0, V, size=B * k)
+    for path in ("stream", "fast"):
+        rep = check_accept(st, oracle_mod, pkg, path=path)
+        assert rep["oracle_mean_accept_len"] == k
 
 
 def test_ragged_input_check(pkg):
@@ -334,7 +376,7 @@ def test_step_replayed_from_a_hip_graph(pkg):
             assert torch.equal(toks, ref_t) and torch.equal(alen, ref_a), (rep, s)
 
 
-@pytest.mark.parametrize("path", ["fast", "vector"])
+@pytest.mark.parametrize("path", ["fast", "stream", "vector"])
 def test_accept_with_padded_row_strides(path, oracle_mod, pkg):
     """Logits and draft-probability rows that sit in wider buffers (row stride > V)."""
     import torch
