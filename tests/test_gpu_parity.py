@@ -107,6 +107,13 @@ def test_config_attention_vector_path(cfg, oracle_mod, pkg):
     check_attention(st, oracle_mod, pkg, path="vector")
 
 
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_config_accept_register_resident_path(cfg, oracle_mod, pkg):
+    # (AUTO takes the streaming kernel for these two: more logits rows than compute units)
+    st = W.make_verify_step(cfg, attention=False)
+    check_accept(st, oracle_mod, pkg, path="fast")
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 5])
 def test_config_accept_stream_path(cfg, oracle_mod, pkg):
     st = W.make_verify_step(cfg, attention=False)
