@@ -6,15 +6,21 @@
 // the draft-probability row is streamed ONCE, nothing is re-read from memory
 // except one 16-byte chunk per thread for the final token search:
 //
-//   1. load the row; greedy rows: argmax (lowest index on ties) and done
-//   2. m = max, Z = sum 2^((l - m) c), c = log2(e) / T  (thread-local maxima first,
-//      then one exchange through LDS)
-//   3. stream q: chunk sums s[it] of r = max(0, 2^((l - m) c) / Z - q) kept in registers
-//   4. per-step block totals (fp64) -> R, tau = u1 * R, the step it* whose running
-//      total first exceeds tau
-//   5. inside step it*: fp64 scan over wavefronts and lanes -> the owning thread,
+//   0. which request owns the row: block scan of spec_lens (its loads are requested
+//      before the row's, LDS-only barriers), no plan kernel in front
+//   1. the row is requested step by step while ONE sweep follows the loads:
+//      m = max and Z = sum 2^((l - m) c), c = log2(e) / T, against a running
+//      per-thread reference, (m, z) pairs merged through LDS;
+//      greedy rows: argmax (lowest index on ties) and done
+//   2. stream q (zero-size descriptor for bonus rows): per-step sums of
+//      r = max(0, 2^((l - m) c) / Z - q), 16-lane DPP sums in fp32, fp64 above
+//   3. one wavefront: per-step block totals -> R, tau = u1 * R, the step it* whose
+//      running total first exceeds tau (lane-parallel fp64 scan)
+//   4. inside step it*: fp64 scan over wavefronts and lanes -> the owning thread,
 //      which walks its 8 elements
 // Per-element arithmetic is fp32; every sum across threads is fp64.
+// The best kernel while every row has a compute unit to itself; with more rows than
+// compute units the streaming kernel (accept_stream.hip) overlaps two rows per unit.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"

@@ -1,16 +1,21 @@
-// Streaming acceptance kernel for 16-bit logits and draft probabilities whose rows do not fit the
-// register-resident kernel (131072 < V <= 524288, V % 8 == 0).  Same rule, same per-row results
-// (flag, candidate) as the other two acceptance kernels; one workgroup of 1024 threads per logits row,
-// 16 bytes = 8 elements per thread per step of 8192:
+// Streaming acceptance kernel for gfx950: 16-bit logits and draft probabilities, V % 8 == 0,
+// V <= 524288.  Same rule and same per-row results (flag, candidate) as the other two acceptance
+// kernels.  It serves vocabularies too large for the register-resident kernel, and any batch with
+// more logits rows than compute units: it needs at most 64 registers per thread and 73 KB of LDS, so
+// TWO workgroups (rows) share a compute unit and one row's compute and latency phases overlap the
+// other's memory phases.
 //
+// One workgroup of 1024 threads per logits row, 16 bytes = 8 elements per thread per step of 8192:
+//   stash    steps 0..3 of the row go from memory straight into LDS (no registers), requested before
+//            anything else; steps 4..7 are kept in registers during sweep 1: half of a 256 KB row
+//            stays on chip
 //   sweep 1  maximum and normaliser on line (running per-thread reference, (m, z) pairs merged);
 //            greedy rows: arg-max (lowest index on ties) and done
-//   sweep 2  the logits again (from the caches: a row is at most 1 MB) with the draft-probability
-//            row: residual mass r = max(0, p - q) per (step, wavefront) in fp64
-//   search   the step holding tau = u1 * R by a lane-parallel scan, then one more read of that
-//            step's two chunks: wavefront, lane, element
-// HBM traffic is the algorithmic minimum when sweep 2 hits the caches; otherwise the logits row counts
-// twice.  Per-element arithmetic is fp32, sums across threads fp64 in a fixed order.
+//   sweep 2  the logits again (resident half from LDS / registers, the rest from the caches) with the
+//            draft-probability row: residual mass r = max(0, p - q) per (step, wavefront) in fp64
+//   search   the step holding tau = u1 * R by a lane-parallel scan, then that step's two chunks once
+//            more: wavefront, lane, element
+// Per-element arithmetic is fp32, sums across threads fp64 in a fixed order.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"
