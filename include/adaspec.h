@@ -26,6 +26,12 @@
  *     first with adaspec_check_ragged_inputs().
  *   - Outputs are fully overwritten.  Results are deterministic: the same
  *     inputs give bit-identical outputs (no floating-point atomics).
+ *   - Host threads: the library keeps no state between calls apart from
+ *     one-time device queries and the timing hooks of
+ *     adaspec_set_timing_events (process-wide, meant for a single-threaded
+ *     benchmark).  Calls from several threads are safe as long as they do not
+ *     share a workspace.  The calls enqueue kernels only (no allocation, no
+ *     memset, no synchronisation), so they can be captured into a HIP graph.
  */
 #ifndef ADASPEC_H
 #define ADASPEC_H

@@ -143,6 +143,8 @@ def _stream_ptr(stream) -> int:
     return int(s.cuda_stream)
 
 
+# Default workspace, one per device, grown on demand.  Callers that issue calls on several streams must
+# pass their own `workspace` per stream: calls that share a workspace have to be ordered on one stream.
 _ws_cache = {}
 
 
