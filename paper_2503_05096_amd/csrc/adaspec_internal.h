@@ -20,14 +20,14 @@ struct AttnPlan {
     int   max_items;        // host-side bound on the number of work items
     int   max_rows;         // (max_spec_len + 1) * G
     // byte offsets into the workspace
-    size_t off_header;      // int32[16]: [0] n_items, [1] ticket counter
+    size_t off_header;      // int32[16]: [0] n_items, [1] ticket counter, [2] rounds of the static schedule
     size_t off_cu_q;        // int32[B + 1]
-    size_t off_row_req;     // int32[TQ]
     size_t off_split_base;  // int32[B + 1]: first item of each request
     size_t off_item_req;    // int32[max_items]
     size_t off_item_order;  // int32[max_items]: items sorted by decreasing length (schedule order)
     size_t off_unit_meta;   // int32[max_items][8] in schedule order: request, split, n_splits, L, n, cu_q, item, 0
     size_t off_row_rec;     // int32[TQ][4] per query row: request, n_splits, first split, row base (j * G)
+    size_t off_sched;       // int32[rounds][W]: unit taken by workgroup w in each round, or -1 (matrix-core kernel)
     size_t off_part_ml;     // float[max_items][Hkv][max_rows][2]  (m in log2 units, l)
     size_t off_part_o;      // float[max_items][Hkv][max_rows][d]
     size_t total_bytes;
@@ -38,6 +38,18 @@ __host__ __device__ inline int split_len_of(int L, int ns, int block_tokens)
 {
     const int per = (L + ns - 1) / ns;
     return (per + block_tokens - 1) / block_tokens * block_tokens;
+}
+
+// Matrix-core kernel: 16-row query tiles one unit holds (1..3), and units per (item, kv head).
+inline int attn_row_tiles(int max_rows)
+{
+    const int t = (max_rows + 15) / 16;
+    return t > 3 ? 3 : (t < 1 ? 1 : t);
+}
+inline int attn_row_groups(int max_rows)
+{
+    const int r = 16 * attn_row_tiles(max_rows);
+    return max_rows > r ? (max_rows + r - 1) / r : 1;
 }
 
 AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path);
@@ -52,7 +64,18 @@ struct AttnArgs {
     AttnPlan plan;
     char *ws;
     hipStream_t stream;
+    // launch shape of the matrix-core kernel (attn_mfma_shape); sched_w = 0 on the vector path
+    int sched_w = 0;          // W: workgroups of the launch = columns of the schedule table
+    int sched_cus = 1;        // compute units of the device
+    int n_row_groups = 1;     // units per (item, kv head)
+    int rows_per_group = 16;  // query rows (times G) one unit covers
 };
+
+// Upper bound on W for which the workspace holds a schedule table.
+constexpr int kMaxSchedW = 1024;
+
+// Fills sched_w / n_row_groups / rows_per_group for the matrix-core kernel's launch of a.dims.
+void attn_mfma_shape(AttnArgs &a);
 
 hipError_t launch_attn_plan(const AttnArgs &a);
 hipError_t launch_attn_vector(const AttnArgs &a);

@@ -79,12 +79,15 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
     size_t off = 0;
     p.off_header = off;     off = align_up(off + 16 * sizeof(int32_t), 256);
     p.off_cu_q = off;       off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
-    p.off_row_req = off;    off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 4, 256);
     p.off_split_base = off; off = align_up(off + (size_t)(d.batch + 1) * 4, 256);
     p.off_item_req = off;   off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
     p.off_item_order = off; off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 4, 256);
     p.off_unit_meta = off;  off = align_up(off + (size_t)(p.max_items > 0 ? p.max_items : 1) * 32, 256);
     p.off_row_rec = off;    off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 16, 256);
+    {   // schedule table: every unit appears once, every round is W <= kMaxSchedW wide
+        const size_t units = (size_t)p.max_items * d.n_kv_heads * attn_row_groups(p.max_rows);
+        p.off_sched = off;  off = align_up(off + (fast_path ? units + kMaxSchedW : 1) * 4, 256);
+    }
     p.off_part_ml = off;
     off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * 2 * sizeof(float), 256);
     p.off_part_o = off;
@@ -158,6 +161,7 @@ int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
     const float scale = dims->scale > 0.0f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
     a.scale_log2 = scale * 1.4426950408889634f;
 
+    if (fast) attn_mfma_shape(a);
     if (dims->plan_mode != ADASPEC_PLAN_REUSE && launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (plan_only) return ADASPEC_OK;
     if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_start[0], a.stream) != hipSuccess)

@@ -96,7 +96,8 @@ template <class T, int RT>
 __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     const char *__restrict__ q, const char *__restrict__ k_pages, const char *__restrict__ v_pages,
     const int32_t *__restrict__ block_table, void *__restrict__ out, int32_t *__restrict__ header,
-    const int32_t *__restrict__ unit_meta, float *__restrict__ part_ml, float *__restrict__ part_o,
+    const int32_t *__restrict__ unit_meta, const int32_t *__restrict__ sched,
+    float *__restrict__ part_ml, float *__restrict__ part_o,
     int Hq, int Hkv, int max_pages_per_req, int max_rows, int n_row_groups, float scale_log2,
     int out_dtype)
 {
@@ -125,15 +126,21 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     const uint32_t v_lane_off = (4 * g) * (kD * 2) + 16 * n16;
 
     // ---- work-unit bookkeeping ----------------------------------------------------------------
-    // Units are listed longest first.  Workgroup w of W takes them in "snake" order
-    // (w, 2W-1-w, 2W+w, ...): every workgroup gets a similar mix of long and short units without
-    // any atomic, and the next unit is known ahead of time so its data can be requested early.
+    // Units are listed longest first and handed out in rounds of W (one unit per workgroup and
+    // round).  Which unit a workgroup takes in a round is a table the plan kernel wrote: it gives
+    // the longest unit of the round to the workgroup with the least work so far.  No atomic is
+    // needed and the next unit is known ahead of time, so its data can be requested early.
     const int W = gridDim.x, wg = blockIdx.x;
+    const int n_rounds = header[2];
     int round = 0;
+    int idx_ahead = wg;                                             // round 0 is the identity
     auto next_unit = [&](Unit &u) -> bool {
-        for (; round * W < total_units; ++round) {
-            const int idx = round * W + ((round & 1) ? (W - 1 - wg) : wg);
-            if (idx >= total_units) continue;
+        for (; round < n_rounds; ++round) {
+            const int idx = idx_ahead;
+            // the entry of the following round is requested together with this unit's record, one
+            // unit before it is needed
+            idx_ahead = round + 1 < n_rounds ? sched[(int64_t)(round + 1) * W + wg] : -1;
+            if (idx < 0 || idx >= total_units) continue;
             const int rg = idx % n_row_groups;
             u.gkv = (idx / n_row_groups) % Hkv;
             const int32_t *mt = unit_meta + 8 * (int64_t)(idx / (n_row_groups * Hkv));
@@ -430,46 +437,80 @@ bool attn_fast_path_supported(const adaspec_attn_dims &d)
     return d.head_dim == kD && (d.dtype == ADASPEC_F16 || d.dtype == ADASPEC_BF16) && d.page_size == 16;
 }
 
+// Resident workgroups of attn_mfma_kernel<T, RT> on the current device: the schedule balances
+// over exactly these.  Queried once per instantiation.
+static int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 256;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
+template <typename T, int RT>
+static int attn_mfma_slots()
+{
+    static int slots = 0;
+    if (slots == 0) {
+        int per_cu = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0) != hipSuccess)
+            per_cu = 1;
+        const int n = device_cus() * (per_cu > 0 ? per_cu : 1);
+        slots = n < kMaxSchedW ? n : kMaxSchedW;
+    }
+    return slots;
+}
+
+template <typename F>
+static void with_instance(int dtype, int rt, F &&f)
+{
+    auto with_rt = [&](auto tag) {
+        switch (rt) {
+        case 1: f(tag, std::integral_constant<int, 1>{}); break;
+        case 2: f(tag, std::integral_constant<int, 2>{}); break;
+        default: f(tag, std::integral_constant<int, 3>{}); break;
+        }
+    };
+    if (dtype == ADASPEC_F16) with_rt(F16{});
+    else with_rt(BF16{});
+}
+
+void attn_mfma_shape(AttnArgs &a)
+{
+    const AttnPlan &p = a.plan;
+    const int rt = attn_row_tiles(p.max_rows);
+    a.n_row_groups = attn_row_groups(p.max_rows);
+    a.rows_per_group = 16 * rt;
+    const int64_t max_units = (int64_t)p.max_items * a.dims.n_kv_heads * a.n_row_groups;
+    int slots = 1;
+    with_instance(a.dims.dtype, rt, [&](auto tag, auto rt_tag) {
+        slots = attn_mfma_slots<decltype(tag), decltype(rt_tag)::value>();
+    });
+    a.sched_w = (int)(max_units < slots ? max_units : slots);
+    a.sched_cus = device_cus();
+}
+
 hipError_t launch_attn_mfma(const AttnArgs &a)
 {
     const AttnPlan &p = a.plan;
     const adaspec_attn_dims &d = a.dims;
-    int rt = ceil_div(p.max_rows, 16);
-    if (rt > 3) rt = 3;
-    const int n_row_groups = ceil_div(p.max_rows, 16 * rt);
-    const int64_t max_units = (int64_t)p.max_items * d.n_kv_heads * n_row_groups;
-    if (max_units == 0) return hipSuccess;
-    auto launch = [&](auto tag, auto rt_tag) {
+    if (a.sched_w <= 0) return hipSuccess;                          // no work item can exist
+    with_instance(d.dtype, attn_row_tiles(p.max_rows), [&](auto tag, auto rt_tag) {
         using T = decltype(tag);
         constexpr int RT = decltype(rt_tag)::value;
-        // one resident "slot" per workgroup: the static snake schedule balances over exactly these
-        static int slots = 0;
-        if (slots == 0) {
-            int dev = 0, cus = 256, per_cu = 1;
-            if (hipGetDevice(&dev) == hipSuccess) {
-                if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
-                if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0) != hipSuccess)
-                    per_cu = 1;
-            }
-            slots = cus * (per_cu > 0 ? per_cu : 1);
-        }
-        const int grid = (int)(max_units < slots ? max_units : slots);
-        hipLaunchKernelGGL((attn_mfma_kernel<T, RT>), dim3(grid), dim3(256), 0, a.stream,
+        hipLaunchKernelGGL((attn_mfma_kernel<T, RT>), dim3(a.sched_w), dim3(256), 0, a.stream,
                            (const char *)a.q, (const char *)a.k_pages, (const char *)a.v_pages,
                            a.block_table, a.out, (int32_t *)(a.ws + p.off_header),
-                           (const int32_t *)(a.ws + p.off_unit_meta), (float *)(a.ws + p.off_part_ml),
-                           (float *)(a.ws + p.off_part_o), d.n_q_heads, d.n_kv_heads, d.max_pages_per_req,
-                           p.max_rows, n_row_groups, a.scale_log2, d.out_dtype);
-    };
-    auto with_rt = [&](auto tag) {
-        switch (rt) {
-        case 1: launch(tag, std::integral_constant<int, 1>{}); break;
-        case 2: launch(tag, std::integral_constant<int, 2>{}); break;
-        default: launch(tag, std::integral_constant<int, 3>{}); break;
-        }
-    };
-    if (d.dtype == ADASPEC_F16) with_rt(F16{});
-    else with_rt(BF16{});
+                           (const int32_t *)(a.ws + p.off_unit_meta), (const int32_t *)(a.ws + p.off_sched),
+                           (float *)(a.ws + p.off_part_ml), (float *)(a.ws + p.off_part_o), d.n_q_heads,
+                           d.n_kv_heads, d.max_pages_per_req, p.max_rows, a.n_row_groups, a.scale_log2,
+                           d.out_dtype);
+    });
     return hipGetLastError();
 }
 

@@ -6,103 +6,217 @@
 namespace adaspec {
 
 constexpr int kPlanThreads = 1024;
+constexpr int kSchedItems = 8192;        // work items whose request and length the kernel keeps on chip
+constexpr int kUnitFixedBlocks = 2;      // fixed cost of a unit (Q load, merge, output), in token blocks
+constexpr int kBalancedRounds = 1;       // last rounds of the schedule that are assigned by accumulated work
+static_assert(kMaxSchedW <= kPlanThreads, "one plan thread per workgroup of the schedule");
 
-// One workgroup.  cu_q = exclusive scan of n_i = spec_lens[i] + 1; split_base =
-// exclusive scan of the per-request split counts ceil(L_i / S); row_req / item_req
-// map a query row / a work item back to its request.  Values are clamped to the
-// host-declared bounds so that inconsistent device data cannot make the library
+__host__ __device__ inline int log2_exact(int v)          // v is a power of two
+{
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+// One workgroup.  cu_q = exclusive scan of n_i = spec_lens[i] + 1; split_base = exclusive scan of
+// the per-request split counts ceil(L_i / S); a work item is one (request, split).  Values are
+// clamped to the host-declared bounds so that inconsistent device data cannot make the library
 // write outside its workspace.
+//
+// W > 0 (matrix-core kernel): writes row_rec, unit_meta, the schedule table and the header.
+// W = 0 (vector kernel): writes cu_q, split_base, item_req, item_order, row_rec and the header.
+//
+// The kernel is a chain of short dependent phases, so what it costs is latency: the barriers
+// between phases wait for LDS traffic only (a full barrier would also wait until every global
+// store of the phase before has been acknowledged, about a microsecond each time), and whatever a
+// later phase needs again stays in LDS.  Only shapes too large for that (more than kPlanThreads
+// requests, more than kSchedItems items) read their own global stores back, behind a full barrier.
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
     const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ spec_lens, int B, int total_q,
-    int max_spec_len, int split_tokens, int block_tokens, int max_items, int G, int32_t *__restrict__ header,
-    int32_t *__restrict__ cu_q, int32_t *__restrict__ row_req, int32_t *__restrict__ split_base,
-    int32_t *__restrict__ item_req, int32_t *__restrict__ item_order, int32_t *__restrict__ unit_meta,
-    int32_t *__restrict__ row_rec)
+    int max_spec_len, int split_log2, int block_log2, int max_items, int G, int32_t *__restrict__ header,
+    int32_t *__restrict__ cu_q, int32_t *__restrict__ split_base, int32_t *__restrict__ item_req,
+    int32_t *__restrict__ item_order, int32_t *__restrict__ unit_meta, int32_t *__restrict__ row_rec,
+    int W, int Hkv, int n_row_groups, int rows_per_group, int32_t *__restrict__ sched, int cus)
 {
     __shared__ int tot_n[kPlanThreads / kWave], tot_s[kPlanThreads / kWave];
     __shared__ int carry[2];
     __shared__ int hist[64];
-    // per-request values of the first kPlanThreads requests stay in LDS: the item phase below then
-    // needs no global round trip for them (later requests, if any, are read back from memory)
-    __shared__ int4 req[kPlanThreads];         // (L, n, cu_q, split_base)
+    __shared__ int4 req[kPlanThreads];         // (L, n, cu_q, split_base) of the first kPlanThreads requests
+    __shared__ uint16_t item_req_l[kSchedItems];                        // request of each item
+    __shared__ uint8_t item_blocks[kSchedItems], item_groups[kSchedItems];   // per SORTED item: token blocks, row groups
+    __shared__ int bins[kPlanThreads], wg_work[kPlanThreads], wave_tot[kPlanThreads / kWave];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int split_tokens = 1 << split_log2, block_tokens = 1 << block_log2;
+    const bool fast = W > 0;
+    const bool items_on_chip = max_items <= kSchedItems && B <= 65535;  // host-side bounds: uniform
+    const bool reqs_on_chip = B <= kPlanThreads;
     if (tid == 0) { carry[0] = 0; carry[1] = 0; }
-    __syncthreads();
+    lds_barrier();
     for (int base = 0; base < B; base += kPlanThreads) {
         const int i = base + tid;
         int n = 0, ns = 0, L = 1;
         if (i < B) {
             n = min(max(spec_lens[i], 0), max_spec_len) + 1;
             L = max(ctx_lens[i], 1);
-            ns = ceil_div(L, split_tokens);
+            ns = (L + split_tokens - 1) >> split_log2;
         }
-        const int inc_n = wave_scan_incl(n, lane), inc_s = wave_scan_incl(ns, lane);
+        const int inc_n = wave_scan_incl_dpp(n), inc_s = wave_scan_incl_dpp(ns);
         if (lane == 63) { tot_n[wv] = inc_n; tot_s[wv] = inc_s; }
-        __syncthreads();
+        lds_barrier();
         int pre_n = carry[0], pre_s = carry[1];
-        for (int w = 0; w < wv; ++w) { pre_n += tot_n[w]; pre_s += tot_s[w]; }
+#pragma unroll
+        for (int w = 0; w < kPlanThreads / kWave; ++w) {   // fixed trip count: the reads go out together
+            pre_n += w < wv ? tot_n[w] : 0;
+            pre_s += w < wv ? tot_s[w] : 0;
+        }
         const int my_q = pre_n + inc_n - n, my_s = pre_s + inc_s - ns;
         if (i < B) {
-            cu_q[i] = my_q;
-            split_base[i] = my_s;
+            if (!fast || !reqs_on_chip) { cu_q[i] = my_q; split_base[i] = my_s; }
             if (base == 0) req[tid] = make_int4(L, n, my_q, my_s);
+            // record for the combine kernel: (request, number of splits, first split, first row index of
+            // this query row inside its (item, kv head) partial block)
             for (int j = 0; j < n; ++j)
-                if (my_q + j < total_q) {
-                    row_req[my_q + j] = i;
-                    // record for the combine kernel: (request, number of splits, first split, first row index of
-                    // this query row inside its (item, kv head) partial block)
+                if (my_q + j < total_q)
                     *reinterpret_cast<int4 *>(row_rec + 4 * (int64_t)(my_q + j)) = make_int4(i, ns, my_s, j * G);
-                }
             for (int s = 0; s < ns; ++s)
-                if (my_s + s < max_items) item_req[my_s + s] = i;
+                if (my_s + s < max_items) {
+                    if (items_on_chip) item_req_l[my_s + s] = (uint16_t)i;
+                    if (!fast || !items_on_chip) item_req[my_s + s] = i;
+                }
         }
-        __syncthreads();
+        lds_barrier();
         if (tid == kPlanThreads - 1) { carry[0] = pre_n + inc_n; carry[1] = pre_s + inc_s; }
-        __syncthreads();
+        lds_barrier();
     }
     if (tid == 0) {
-        cu_q[B] = carry[0];
-        split_base[B] = carry[1];
+        if (!fast) { cu_q[B] = carry[0]; split_base[B] = carry[1]; }
         header[0] = min(carry[1], max_items);   // number of work items
         header[1] = 0;                          // ticket counter of the vector kernel
     }
     // Schedule order: longest items first (counting sort on the length in token blocks), so that
     // the workgroups that take units last get the short items and the tail of the launch is short.
     const int n_items = min(carry[1], max_items);
-    const int nbins = min(64, max(1, split_tokens / block_tokens));
+    const int per_split = split_tokens >> block_log2;          // token blocks of a full split
+    const int nbins = min(64, max(1, per_split));
     if (tid < 64) hist[tid] = 0;
-    __syncthreads();
-    auto request_of = [&](int i) -> int4 {
-        if (i < kPlanThreads) return req[i];
-        return make_int4(max(ctx_lens[i], 1), min(max(spec_lens[i], 0), max_spec_len) + 1, cu_q[i], split_base[i]);
-    };
-    auto bin_of = [&](int item, const int4 &rq) {
-        const int L = rq.x;
-        const int ns = ceil_div(L, split_tokens), s = item - rq.w;
+    if (items_on_chip && reqs_on_chip) lds_barrier();
+    else __syncthreads();                      // the phases below read global stores of the one above
+    struct Item { int4 rq; int i, s, blocks, bin; };
+    auto item_info = [&](int item) -> Item {
+        Item it;
+        it.i = items_on_chip ? (int)item_req_l[item] : item_req[item];
+        if (it.i < kPlanThreads) it.rq = req[it.i];
+        else
+            it.rq = make_int4(max(ctx_lens[it.i], 1), min(max(spec_lens[it.i], 0), max_spec_len) + 1, cu_q[it.i],
+                              split_base[it.i]);
+        const int L = it.rq.x, ns = (L + split_tokens - 1) >> split_log2;
+        it.s = item - it.rq.w;
         const int slen = split_len_of(L, ns, block_tokens);
-        const int len = min(L, (s + 1) * slen) - s * slen;
-        const int scaled = (int)(((int64_t)max(len, 1) * nbins + split_tokens - 1) / split_tokens);
-        return nbins - min(max(scaled, 1), nbins);   // bin 0 = longest
+        const int len = min(L, (it.s + 1) * slen) - it.s * slen;
+        it.blocks = (max(len, 1) + block_tokens - 1) >> block_log2;
+        // bin 0 = longest; with more than 64 blocks per split the length is scaled down to 64 bins
+        const int scaled = per_split <= 64 ? it.blocks
+                                           : (int)(((int64_t)max(len, 1) * nbins + split_tokens - 1) >> split_log2);
+        it.bin = nbins - min(max(scaled, 1), nbins);
+        return it;
     };
+    Item mine;                                  // this thread's first item, kept for the second pass
+    mine.i = -1;
     for (int item = tid; item < n_items; item += kPlanThreads) {
-        const int4 rq = request_of(item_req[item]);
-        atomicAdd(&hist[bin_of(item, rq)], 1);
+        const Item it = item_info(item);
+        if (item == tid) mine = it;
+        atomicAdd(&hist[it.bin], 1);
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < 64) {                            // exclusive prefix over the bins (one wavefront)
         const int c = tid < nbins ? hist[tid] : 0;
-        const int inc = wave_scan_incl(c, lane);
+        const int inc = wave_scan_incl_dpp(c);
         hist[tid] = inc - c;
     }
-    __syncthreads();
+    lds_barrier();
     for (int item = tid; item < n_items; item += kPlanThreads) {
-        const int i = item_req[item];
-        const int4 rq = request_of(i);
-        const int pos = atomicAdd(&hist[bin_of(item, rq)], 1);
-        item_order[pos] = item;
+        const Item it = item == tid ? mine : item_info(item);
+        const int pos = atomicAdd(&hist[it.bin], 1);
+        if (!fast) { item_order[pos] = item; continue; }
         int32_t *m = unit_meta + 8 * (int64_t)pos;
-        *reinterpret_cast<int4 *>(m) = make_int4(i, item - rq.w, ceil_div(rq.x, split_tokens), rq.x);
-        *reinterpret_cast<int4 *>(m + 4) = make_int4(rq.y, rq.z, item, 0);
+        *reinterpret_cast<int4 *>(m) =
+            make_int4(it.i, it.s, (it.rq.x + split_tokens - 1) >> split_log2, it.rq.x);
+        *reinterpret_cast<int4 *>(m + 4) = make_int4(it.rq.y, it.rq.z, item, 0);
+        if (items_on_chip) {
+            item_blocks[pos] = (uint8_t)min(it.blocks, 255);
+            item_groups[pos] = (uint8_t)min(ceil_div(it.rq.y * G, rows_per_group), 255);
+        }
+    }
+    if (!fast) return;
+
+    // ---- static schedule of the matrix-core kernel ---------------------------------------------
+    // Units (item, kv head, row group) in the sorted item order are handed out in rounds of W, one
+    // per workgroup and round; thread w plays workgroup w.  Rounds alternate direction (round 0 is
+    // the identity, round 1 the reverse, ...), which evens out the work when every workgroup takes
+    // the same number of units.  The last kBalancedRounds rounds are assigned by accumulated work
+    // instead.  What has to be even there is the work per COMPUTE UNIT, not per workgroup: the
+    // workgroups resident on one compute unit share its load pipeline (the older one is served
+    // first), and a compute unit finishes when its total is done.  Workgroups w, w + cus,
+    // w + 2 cus, ... land on the same compute unit (the dispatcher fills the compute units in
+    // order, one workgroup each, then starts over), so such a round is cut into sub-rounds of
+    // `cus` units: in each the j-th longest unit goes to the compute unit with the j-th least
+    // work, found by a counting sort.  The table only decides who computes what; results do not
+    // depend on it, nor on the assumed placement.
+    const int units_per_item = Hkv * n_row_groups;
+    const int upi_log2 = (units_per_item & (units_per_item - 1)) == 0 ? log2_exact(units_per_item) : -1;
+    const int total_units = n_items * units_per_item;
+    const int rounds = ceil_div(total_units, W);
+    if (tid == 0) header[2] = rounds;
+    wg_work[tid] = 0;
+    int shift = 0;                              // compute-unit work >> shift fits the bins
+    {
+        const int64_t most = (int64_t)rounds * ceil_div(W, cus) * (255 + kUnitFixedBlocks);
+        while ((most >> shift) >= kPlanThreads) ++shift;
+    }
+    lds_barrier();                             // item_blocks / item_groups are complete
+    auto take = [&](int r, int idx) {          // workgroup tid takes unit idx (if it exists) in round r
+        int v = -1;
+        if (idx < total_units) {
+            v = idx;
+            if (items_on_chip) {
+                const int pos = upi_log2 >= 0 ? idx >> upi_log2 : idx / units_per_item;
+                const int rg = n_row_groups == 1 ? 0 : idx % n_row_groups;
+                if (rg < item_groups[pos]) wg_work[tid] += item_blocks[pos] + kUnitFixedBlocks;
+            }
+        }
+        sched[(int64_t)r * W + tid] = v;
+    };
+    for (int r = 0; r < rounds; ++r) {
+        if (!(r >= 1 && items_on_chip && rounds - r <= kBalancedRounds)) {
+            if (tid < W) take(r, r * W + ((r & 1) ? (W - 1 - tid) : tid));
+            continue;
+        }
+        for (int base = 0; base < W; base += cus) {
+            const int c = tid - base;
+            const bool active = c >= 0 && c < min(cus, W - base);
+            if (r * W + base >= total_units) {  // nothing left for this sub-round
+                if (active) take(r, total_units);
+                continue;
+            }
+            lds_barrier();                      // wg_work of everything assigned so far
+            bins[tid] = 0;
+            int cu_work = 0;
+            if (active)
+                for (int w = c; w < W; w += cus) cu_work += wg_work[w];
+            const int key = min(cu_work >> shift, kPlanThreads - 1);
+            lds_barrier();
+            if (active) atomicAdd(&bins[key], 1);
+            lds_barrier();
+            const int cnt = bins[tid], inc = wave_scan_incl_dpp(cnt);
+            if (lane == 63) wave_tot[wv] = inc;
+            lds_barrier();
+            int pre = 0;
+#pragma unroll
+            for (int w = 0; w < kPlanThreads / kWave; ++w) pre += w < wv ? wave_tot[w] : 0;
+            bins[tid] = pre + inc - cnt;
+            lds_barrier();
+            if (active) take(r, r * W + base + atomicAdd(&bins[key], 1));
+        }
     }
 }
 
@@ -110,13 +224,14 @@ hipError_t launch_attn_plan(const AttnArgs &a)
 {
     const AttnPlan &p = a.plan;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, a.stream, a.ctx_lens,
-                       a.spec_lens, a.dims.batch, a.dims.total_q, a.dims.max_spec_len, p.split_tokens,
-                       p.block_tokens, p.max_items, a.dims.n_q_heads / a.dims.n_kv_heads,
-                       (int32_t *)(a.ws + p.off_header),
-                       (int32_t *)(a.ws + p.off_cu_q), (int32_t *)(a.ws + p.off_row_req),
-                       (int32_t *)(a.ws + p.off_split_base), (int32_t *)(a.ws + p.off_item_req),
-                       (int32_t *)(a.ws + p.off_item_order), (int32_t *)(a.ws + p.off_unit_meta),
-                       (int32_t *)(a.ws + p.off_row_rec));
+                       a.spec_lens, a.dims.batch, a.dims.total_q, a.dims.max_spec_len,
+                       log2_exact(p.split_tokens), log2_exact(p.block_tokens), p.max_items,
+                       a.dims.n_q_heads / a.dims.n_kv_heads, (int32_t *)(a.ws + p.off_header),
+                       (int32_t *)(a.ws + p.off_cu_q), (int32_t *)(a.ws + p.off_split_base),
+                       (int32_t *)(a.ws + p.off_item_req), (int32_t *)(a.ws + p.off_item_order),
+                       (int32_t *)(a.ws + p.off_unit_meta), (int32_t *)(a.ws + p.off_row_rec), a.sched_w,
+                       a.dims.n_kv_heads, a.n_row_groups, a.rows_per_group, (int32_t *)(a.ws + p.off_sched),
+                       a.sched_cus);
     return hipGetLastError();
 }
 

@@ -103,6 +103,20 @@ __device__ __forceinline__ int wave_scan_incl(int v, int lane)
     return v;
 }
 
+// The same inclusive scan with data-parallel-primitive moves instead of LDS permutes: no LDS round
+// trip per step, which is what a latency-bound kernel pays for.  Lanes that a shift leaves without a
+// source, and rows that a broadcast does not address, add 0.
+__device__ __forceinline__ int wave_scan_incl_dpp(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8 -> scan inside each row of 16
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // (value, index) max with the LOWEST index winning ties
 struct ArgMax { float v; int i; };
 __device__ __forceinline__ ArgMax argmax_merge(ArgMax a, ArgMax b)

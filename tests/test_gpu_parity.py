@@ -315,6 +315,22 @@ def test_more_than_1024_requests(oracle_mod, pkg):
     check_accept(st, oracle_mod, pkg, path="vector")
 
 
+def test_more_work_items_than_the_plan_keeps_on_chip(oracle_mod, pkg):
+    """One request with a very long context makes the block table wide, so the host-side bound on the work
+    items (requests x splits of the widest context) exceeds what the plan kernel holds in LDS: it then reads
+    its item list back from global memory and hands the units out without the length-aware last round."""
+    rng = np.random.default_rng(9000)
+    B = 1500
+    spec = rng.integers(0, 4, B).astype(np.int32)
+    ctx = (rng.integers(1, 60, B) + spec + 1).astype(np.int32)
+    ctx[[7, 1203]] = [12288 - 5, 4097]               # 6 and 3 splits of 2048 tokens; 1500 x 6 = 9000 items bound
+    st = W.make_custom_step(9000, ctx_lens=ctx, spec_lens=spec, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                            dtype="bf16", vocab=256, logits_dtype="bf16", temperature=1.0, name="b1500-wide",
+                            acceptance=False)
+    assert st.block_table.shape[1] * 16 >= 12288
+    check_attention(st, oracle_mod, pkg)
+
+
 def test_attention_plan_reuse_across_layers(pkg):
     """The ragged metadata is built once and reused by the attention calls of further layers (other Q, K, V,
     same block table and lengths): every layer must equal a self-contained call bit for bit."""
