@@ -93,7 +93,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg4g", "cfg5"])
-    ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast", "stream"],
+    ap.add_argument("--path", default="auto", choices=["auto", "vector", "fast", "stream", "two_pass"],
                     help="kernel family; 'stream' selects the streaming acceptance kernel (attention stays on auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=3,
@@ -125,7 +125,7 @@ def main() -> int:
     from tests.harness import to_device
 
     cfg = int(args.workload[3])
-    attn_path = "auto" if args.path == "stream" else args.path
+    attn_path = "auto" if args.path in ("stream", "two_pass") else args.path
     st = W.make_verify_step(cfg, greedy=args.workload.endswith("g"), poison=False)
     nbytes = W.algorithmic_bytes(st)
     torch.cuda.set_device(0)

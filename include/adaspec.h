@@ -62,9 +62,14 @@ typedef enum { ADASPEC_F32 = 0, ADASPEC_F16 = 1, ADASPEC_BF16 = 2 } adaspec_dtyp
  * one of them (ADASPEC_ERR_UNSUPPORTED if the shape does not fit it). */
 typedef enum {
     ADASPEC_PATH_AUTO = 0, ADASPEC_PATH_VECTOR = 1, ADASPEC_PATH_FAST = 2,
-    ADASPEC_PATH_STREAM = 3   /* adaspec_accept only: the streaming 16-bit kernel (V up to 524288), which AUTO
+    ADASPEC_PATH_STREAM = 3,  /* adaspec_accept only: the streaming 16-bit kernel (V up to 524288), which AUTO
                                  picks for vocabularies too large for the register-resident kernel and for
                                  batches with more logits rows than the device has compute units */
+    ADASPEC_PATH_TWO_PASS = 4 /* adaspec_accept only, same shapes as ADASPEC_PATH_FAST: first the accept test
+                                 of every draft row (one read of its logits row), then per request the
+                                 sampling step on its first rejected row, or on its bonus row, alone.  Rows
+                                 after a rejection are not read; the draft-probability row is read only
+                                 where a token is recovered from the residual distribution. */
 } adaspec_path;
 
 /* ------------------------------------------------------------------------
@@ -177,12 +182,17 @@ size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims);
  * temperature   [B] float32 >= 0, per request
  * out_tokens    [B][out_stride] int32: a_i accepted drafts, one recovered/bonus token, then -1
  * out_accept_len[B] int32: a_i in [0, k_i]; request i emitted a_i + 1 tokens
- * Rows after a request's first rejection are still evaluated (the rows are independent;
- * the sequential rule is applied to the per-row results afterwards).
- * The register-resident path needs 16-bit logits/probs of one type, V % 8 == 0, V <= 131072,
- * strides % 8 == 0 and 16-byte aligned base pointers; the streaming path takes the same up to
- * V <= 524288 (it reads the logits row twice, the second time from the caches); anything else runs
- * on the vector path.
+ * The per-row paths (vector, register-resident, streaming) evaluate every row, also those after a
+ * request's first rejection (the rows are independent), and apply the sequential rule to the
+ * per-row results afterwards.  The two-pass path judges every draft row first and then runs the
+ * sampling step only on the one row per request that decides its token.  All paths give the same
+ * outputs.
+ * The register-resident and two-pass paths need 16-bit logits/probs of one type, V % 8 == 0,
+ * V <= 131072, strides % 8 == 0 and 16-byte aligned base pointers; the streaming path takes the
+ * same up to V <= 524288 (it reads the logits row twice, the second time from the caches);
+ * anything else runs on the vector path.  AUTO: two-pass when it fits and there are more logits
+ * rows than compute units, register-resident when it fits, streaming for larger vocabularies,
+ * else vector.
  */
 int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const int32_t *draft_tokens, const float *uniforms,

@@ -17,8 +17,9 @@ F32, F16, BF16 = 0, 1, 2
 PATH_AUTO, PATH_VECTOR, PATH_FAST = 0, 1, 2
 PLAN_BUILD_AND_RUN, PLAN_BUILD_ONLY, PLAN_REUSE = 0, 1, 2
 _PLAN = {"run": PLAN_BUILD_AND_RUN, "build": PLAN_BUILD_ONLY, "reuse": PLAN_REUSE}
-PATH_STREAM = 3
-_PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream": PATH_STREAM}
+PATH_STREAM, PATH_TWO_PASS = 3, 4
+_PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream": PATH_STREAM,
+          "two_pass": PATH_TWO_PASS}
 
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",

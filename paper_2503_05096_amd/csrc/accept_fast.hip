@@ -41,20 +41,73 @@ struct FastScratch {
     int    row_i, row_j, row_k;
     float  row_T;
     int    first_hit, last_pos;
+    int    ahead[kFW];                  // resolve mode: rows of the requests in front, per wavefront
 };
 
-template <class DT, int ITER>
+// kResolve = false: one workgroup per logits row; writes the row's flag and candidate, the emit kernel
+// applies the sequential rule afterwards.
+// kResolve = true: second pass of the two-pass form, one workgroup per REQUEST.  The first pass
+// (accept_stream_kernel in test-only mode) has left the flag of every draft row; this pass finds the
+// request's first rejected draft (or its bonus row), runs the sampling part of the rule on that one
+// row only, and writes the request's outputs itself.  Rows after a rejection are never read, accepted
+// rows are read once (by the first pass), and no emit kernel is needed.
+template <class DT, int ITER, bool kResolve>
 __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const float *__restrict__ uniforms,
     const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature, int B, int V,
     int max_spec_len, int64_t lstride, int64_t pstride, int32_t *__restrict__ row_flag,
-    int32_t *__restrict__ row_cand)
+    int32_t *__restrict__ row_cand, int out_stride, int32_t *__restrict__ out_tokens,
+    int32_t *__restrict__ out_accept_len)
 {
     using P = Pair16<DT>;
     __shared__ FastScratch sm;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int r = blockIdx.x;
+    int r = blockIdx.x;
+    int ri = 0, j = 0, k = 0;
+    float T = 0.f;
+    if constexpr (kResolve) {
+        // request i = blockIdx.x: its first row (sum of n over the requests in front), k and T
+        const int i = blockIdx.x;
+        int ahead = 0;
+        for (int base = 0; base < i; base += kFT) {
+            const int idx = base + tid;
+            if (idx < i) ahead += min(max(spec_lens[idx], 0), max_spec_len) + 1;
+        }
+        k = min(max(spec_lens[i], 0), max_spec_len);          // uniform: scalar loads
+        T = temperature[i];
+        ahead = wave_sum(ahead);
+        if (lane == 0) sm.ahead[wv] = ahead;
+        lds_barrier();
+        int start = 0;
+#pragma unroll
+        for (int w = 0; w < kFW; ++w) start += sm.ahead[w];
+        start = __builtin_amdgcn_readfirstlane(start);
+        // the first rejected draft (every wavefront looks for itself: no second barrier)
+        int a = k;
+        for (int j0 = 0; j0 < k; j0 += kWave) {
+            const int f = j0 + lane < k ? row_flag[start + j0 + lane] : 1;
+            const unsigned long long rej = __ballot(f == 0);
+            if (rej) { a = j0 + (int)__builtin_ctzll(rej); break; }
+        }
+        a = __builtin_amdgcn_readfirstlane(a);
+        ri = i; j = a; r = start + a;
+        if (wv == 0) {                        // everything but the sampled token: accepted drafts, padding, length
+            int32_t *o = out_tokens + (int64_t)i * out_stride;
+            for (int jj = lane; jj < out_stride; jj += kWave)
+                if (jj != a) o[jj] = jj < a ? draft_tokens[start - i + jj] : -1;
+            if (lane == 0) out_accept_len[i] = a;
+        }
+        if (T == 0.0f && a < k) {             // greedy and rejected: the first pass left the row's arg-max
+            if (tid == 0) out_tokens[(int64_t)i * out_stride + a] = row_cand[r];
+            return;
+        }
+    }
+    // the row's result: its candidate token (per-row form) or the request's token at position j
+    auto put_cand = [&](int cand) {
+        if constexpr (kResolve) out_tokens[(int64_t)ri * out_stride + j] = cand;
+        else row_cand[r] = cand;
+    };
     const int nchunks = V >> 3;
     const char *lrow = logits + (int64_t)r * lstride * 2;
     const uint32_t tid16 = (uint32_t)tid * 16u;
@@ -83,9 +136,11 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     // so anything asked for after the row would only be seen once the whole row has arrived)
     int n_first = 0;
     float t_first = 0.f;
-    if (tid < B) {
-        n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
-        t_first = temperature[tid];           // the owner of the row's request publishes it with (i, j, k)
+    if constexpr (!kResolve) {
+        if (tid < B) {
+            n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
+            t_first = temperature[tid];       // the owner of the row's request publishes it with (i, j, k)
+        }
     }
     // Only the first kLPre steps of the row are requested here.  A wavefront executes in order and a
     // load instruction is held back while the memory pipeline of the compute unit is full, so a
@@ -101,7 +156,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
 
     // ---- which request owns row r?  (while the loads travel)  Block scan of n_i = k_i + 1 over the
     // requests, 1024 at a time; the thread whose request covers r publishes (i, j, k).
-    {
+    if constexpr (!kResolve) {
         int carry = 0;
         for (int base = 0; base < B; base += kFT) {
             const int i = base + tid;
@@ -126,11 +181,12 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             carry = tot;
             if (r < carry) break;
         }
+        ri = __builtin_amdgcn_readfirstlane(sm.row_i);       // wave-uniform: the loads below are scalar
+        j = __builtin_amdgcn_readfirstlane(sm.row_j);
+        k = __builtin_amdgcn_readfirstlane(sm.row_k);
+        T = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm.row_T)));
     }
-    const int ri = __builtin_amdgcn_readfirstlane(sm.row_i), j = __builtin_amdgcn_readfirstlane(sm.row_j),
-              k = __builtin_amdgcn_readfirstlane(sm.row_k);   // wave-uniform: the loads below are scalar
     const bool bonus = j >= k;
-    const float T = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm.row_T)));
     const char *prow = probs + (int64_t)(r - ri) * pstride * 2;
     const bool sampled = T != 0.0f;
     const bool has_q = sampled && !bonus;
@@ -164,8 +220,8 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             ArgMax a{sm.av[0], sm.ai[0]};
             for (int w = 1; w < kFW; ++w) a = argmax_merge(a, ArgMax{sm.av[w], sm.ai[w]});
             if (a.i >= V) a.i = 0;
-            row_flag[r] = bonus ? 1 : (draft_tokens[r - ri] == a.i);
-            row_cand[r] = a.i;
+            if constexpr (!kResolve) row_flag[r] = bonus ? 1 : (draft_tokens[r - ri] == a.i);
+            put_cand(a.i);
         }
         return;
     }
@@ -207,7 +263,8 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     // counter that cannot tell them apart, so an earlier request would have made the temperature
     // above wait for this load as well.  It arrives while the block result is being exchanged.
     __builtin_amdgcn_sched_barrier(0);
-    const int x = bonus ? -1 : draft_tokens[r - ri];
+    int x = -1;
+    if constexpr (!kResolve) x = bonus ? -1 : draft_tokens[r - ri];
     {
         const float mw = wave_max(m_run);
         const float zw = wave_sum(zt * __builtin_amdgcn_exp2f((m_run - mw) * c));
@@ -269,9 +326,11 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     // pass, so nobody waits for them.
     uint32_t lw_x = 0, qw_x = 0;
     const float u_acc = uniforms[2 * (int64_t)r], u_draw = uniforms[2 * (int64_t)r + 1];
-    if (!bonus) {
-        lw_x = reinterpret_cast<const uint32_t *>(lrow)[x >> 1];
-        qw_x = reinterpret_cast<const uint32_t *>(prow)[x >> 1];
+    if constexpr (!kResolve) {
+        if (!bonus) {
+            lw_x = reinterpret_cast<const uint32_t *>(lrow)[x >> 1];
+            qw_x = reinterpret_cast<const uint32_t *>(prow)[x >> 1];
+        }
     }
 
     // ---- 3./4. residual mass per step, block totals, the step that holds tau ------------------
@@ -333,7 +392,7 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
     }
     const double tau = sm.tau, before = sm.before;
 
-    if (tid == 0) {                           // accept test, second half
+    if (!kResolve && tid == 0) {              // accept test, second half
         int flag = 1;
         if (!bonus) {
             const float lx = (x & 1) ? P::hi(lw_x) : P::lo(lw_x);
@@ -397,9 +456,9 @@ __global__ __launch_bounds__(kFT) void accept_fast_kernel(
             if (pick < 0 && rv[e] > 0.f && cum > tau) pick = e;
         }
         if (pick < 0) pick = lastpos < 0 ? 0 : lastpos;
-        row_cand[r] = cstar * 8 + pick;
+        put_cand(cstar * 8 + pick);
     }
-    if (owner < 0 && tid == 0) row_cand[r] = 0;     // no mass anywhere (non-finite input): stay defined
+    if (owner < 0 && tid == 0) put_cand(0);         // no mass anywhere (non-finite input): stay defined
 }
 
 bool accept_fast_path_supported(const adaspec_accept_dims &d, const void *logits, const void *probs)
@@ -411,7 +470,8 @@ bool accept_fast_path_supported(const adaspec_accept_dims &d, const void *logits
     return true;
 }
 
-hipError_t launch_accept_fast(const AcceptArgs &a)
+template <bool kResolve>
+static hipError_t launch_fast_kernel(const AcceptArgs &a)
 {
     const adaspec_accept_dims &d = a.dims;
     if (d.total_q == 0) return hipSuccess;
@@ -419,11 +479,13 @@ hipError_t launch_accept_fast(const AcceptArgs &a)
     auto launch = [&](auto tag, auto it_tag) {
         using DT = decltype(tag);
         constexpr int ITER = decltype(it_tag)::value;
-        hipLaunchKernelGGL((accept_fast_kernel<DT, ITER>), dim3(d.total_q), dim3(kFT), 0, a.stream,
+        hipLaunchKernelGGL((accept_fast_kernel<DT, ITER, kResolve>), dim3(kResolve ? d.batch : d.total_q),
+                           dim3(kFT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.uniforms,
                            a.spec_lens, a.temperature, d.batch, d.vocab, d.max_spec_len,
                            d.logits_row_stride, d.probs_row_stride,
-                           (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand));
+                           (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand),
+                           d.out_stride, a.out_tokens, a.out_accept_len);
     };
     auto with_it = [&](auto tag) {
         if (steps <= 4) launch(tag, std::integral_constant<int, 4>{});
@@ -434,5 +496,10 @@ hipError_t launch_accept_fast(const AcceptArgs &a)
     else with_it(BF16{});
     return hipGetLastError();
 }
+
+hipError_t launch_accept_fast(const AcceptArgs &a) { return launch_fast_kernel<false>(a); }
+
+// Second pass of the two-pass form (after launch_accept_test): one workgroup per request.
+hipError_t launch_accept_resolve(const AcceptArgs &a) { return launch_fast_kernel<true>(a); }
 
 }  // namespace adaspec

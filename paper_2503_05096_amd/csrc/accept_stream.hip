@@ -58,7 +58,10 @@ __device__ __forceinline__ uint4 kept_step(int s, const uint4 &k0, const uint4 &
     return v;
 }
 
-template <class DT>
+// kTestOnly: the first pass of the two-pass form (see accept_fast.hip, resolve mode).  Only draft rows
+// are judged: sweep 1, the accept test, the flag (greedy rows also leave their arg-max as candidate),
+// and the workgroup is done; bonus rows leave at once.  Nothing of sweep 2 is compiled in.
+template <class DT, bool kTestOnly>
 __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const float *__restrict__ uniforms,
@@ -132,9 +135,26 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
               k = __builtin_amdgcn_readfirstlane(sm.row_k);
     const float T = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm.row_T)));
     const bool bonus = j >= k;
+    if constexpr (kTestOnly) {
+        if (bonus) {                          // not judged here; the stash loads must have landed before the
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // workgroup gives its LDS back
+            return;
+        }
+    }
     const int x = bonus ? -1 : draft_tokens[r - ri];
     const char *prow = probs + (int64_t)(r - ri) * pstride * 2;
     if (tid == 0) { sm.first_hit = kST; sm.last_pos = -1; }
+    // test-only form: everything the accept test needs is requested here (scalar loads, the same for the
+    // whole workgroup), one sweep ahead of its use
+    uint32_t lw_t = 0, qw_t = 0;
+    float u_t = 0.f;
+    if constexpr (kTestOnly) {
+        if (T != 0.0f) {
+            lw_t = reinterpret_cast<const uint32_t *>(lrow)[x >> 1];
+            qw_t = reinterpret_cast<const uint32_t *>(prow)[x >> 1];
+            u_t = uniforms[2 * (int64_t)r];
+        }
+    }
 
     if (T == 0.0f) {
         ArgMax best{-INFINITY, V};
@@ -218,6 +238,15 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
     const float invZ = (float)(1.0 / Zd);
 
     // accept test (scalar loads: x is the same for the whole workgroup)
+    if constexpr (kTestOnly) {
+        if (tid == 0) {
+            const float lx = (x & 1) ? P::hi(lw_t) : P::lo(lw_t);
+            const float qx = (x & 1) ? P::hi(qw_t) : P::lo(qw_t);
+            const float px = __builtin_amdgcn_exp2f(fmaf(lx, c, -mc)) * invZ;
+            row_flag[r] = (qx > 0.f) ? (u_t < px / qx) : 1;
+        }
+        return;
+    }
     if (tid == 0) {
         int flag = 1;
         if (!bonus) {
@@ -340,7 +369,8 @@ bool accept_stream_path_supported(const adaspec_accept_dims &d, const void *logi
     return true;
 }
 
-hipError_t launch_accept_stream(const AcceptArgs &a)
+template <bool kTestOnly>
+static hipError_t launch_stream_kernel(const AcceptArgs &a)
 {
     const adaspec_accept_dims &d = a.dims;
     if (d.total_q == 0) return hipSuccess;
@@ -349,12 +379,12 @@ hipError_t launch_accept_stream(const AcceptArgs &a)
         using DT = decltype(tag);
         static bool configured = false;        // more than 64 KB of LDS per workgroup has to be asked for once
         if (!configured) {
-            if (hipFuncSetAttribute((const void *)accept_stream_kernel<DT>,
+            if (hipFuncSetAttribute((const void *)accept_stream_kernel<DT, kTestOnly>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kStashBytes) != hipSuccess)
                 return;
             configured = true;
         }
-        hipLaunchKernelGGL((accept_stream_kernel<DT>), dim3(d.total_q), dim3(kST), kStashBytes, a.stream,
+        hipLaunchKernelGGL((accept_stream_kernel<DT, kTestOnly>), dim3(d.total_q), dim3(kST), kStashBytes, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.uniforms,
                            a.spec_lens, a.temperature, d.batch, d.vocab, d.max_spec_len,
                            d.logits_row_stride, d.probs_row_stride,
@@ -363,6 +393,15 @@ hipError_t launch_accept_stream(const AcceptArgs &a)
     if (d.logits_dtype == ADASPEC_F16) launch(F16{});
     else launch(BF16{});
     return hipGetLastError();
+}
+
+hipError_t launch_accept_stream(const AcceptArgs &a) { return launch_stream_kernel<false>(a); }
+
+// First pass of the two-pass form: flags of the draft rows (and arg-max candidates of greedy ones).
+hipError_t launch_accept_test(const AcceptArgs &a)
+{
+    if (a.dims.total_draft == 0) return hipSuccess;
+    return launch_stream_kernel<true>(a);
 }
 
 }  // namespace adaspec

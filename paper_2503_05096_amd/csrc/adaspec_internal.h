@@ -113,6 +113,9 @@ hipError_t launch_accept_fast(const AcceptArgs &a);
 hipError_t launch_accept_emit(const AcceptArgs &a);
 bool accept_stream_path_supported(const adaspec_accept_dims &d, const void *logits, const void *probs);
 hipError_t launch_accept_stream(const AcceptArgs &a);
+// two-pass form: flags of the draft rows, then one workgroup per request (sampling + outputs)
+hipError_t launch_accept_test(const AcceptArgs &a);
+hipError_t launch_accept_resolve(const AcceptArgs &a);
 
 hipError_t launch_check_ragged(const int32_t *block_table, const int32_t *ctx_lens,
                                const int32_t *spec_lens, const adaspec_attn_dims &d,

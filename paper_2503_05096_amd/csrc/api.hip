@@ -106,7 +106,7 @@ static int validate_accept_dims(const adaspec_accept_dims *d)
     if (!dtype_ok(d->logits_dtype) || !dtype_ok(d->probs_dtype)) return ADASPEC_ERR_DTYPE;
     if (d->logits_row_stride < d->vocab || d->probs_row_stride < d->vocab) return ADASPEC_ERR_DIM;
     if (d->out_stride < d->max_spec_len + 1) return ADASPEC_ERR_DIM;
-    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_STREAM) return ADASPEC_ERR_DIM;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_TWO_PASS) return ADASPEC_ERR_DIM;
     return ADASPEC_OK;
 }
 
@@ -199,12 +199,17 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     const bool stream_ok = accept_stream_path_supported(*dims, target_logits, draft_probs);
     if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
     if (dims->path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
-    // AUTO: the register-resident kernel holds one row per compute unit and never re-reads it, which wins
-    // while every row has a compute unit to itself; with more rows than compute units the streaming kernel
-    // (two rows per compute unit, half of each row re-read from the caches) overlaps the rows' phases and
-    // wins (measured on MI355X: 510 rows of V = 128256: 60 vs 66 us; 237 rows: 43 vs 37 us).
-    bool fast = fast_ok && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_FAST);
-    if (fast && dims->path == ADASPEC_PATH_AUTO && stream_ok && dims->total_q > compute_units()) fast = false;
+    const bool two_pass_ok = fast_ok && stream_ok;
+    if (dims->path == ADASPEC_PATH_TWO_PASS && !two_pass_ok) return ADASPEC_ERR_UNSUPPORTED;
+    // AUTO: with at most one logits row per compute unit every row runs at once and a row's own latency is
+    // all there is: the single-pass register-resident kernel is the shortest chain.  With more rows than
+    // compute units the total work counts, and the two-pass form does about half of it (measured on MI355X,
+    // V = 128256: 510 rows 56 us against 60 + 4.6 us for the streaming kernel and the emit kernel; 227 rows
+    // 44 against 35 us).
+    const bool two_pass = two_pass_ok && (dims->path == ADASPEC_PATH_TWO_PASS ||
+                                          (dims->path == ADASPEC_PATH_AUTO && dims->total_q > compute_units()));
+    // A row that does not fit the registers of one workgroup (V > 131072) goes to the streaming kernel.
+    const bool fast = fast_ok && !two_pass && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_FAST);
     const bool streaming = !fast && stream_ok && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_STREAM);
     AcceptArgs a;
     a.plan = make_accept_plan(*dims);
@@ -215,6 +220,16 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     a.dims = *dims; a.ws = static_cast<char *>(workspace);
     a.stream = static_cast<hipStream_t>(stream);
 
+    if (two_pass) {
+        // the flags of the draft rows, then one workgroup per request: sampling on the one row that
+        // decides its token, and the request's outputs (no emit kernel)
+        if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
+            return ADASPEC_ERR_HIP;
+        if (launch_accept_test(a) != hipSuccess || launch_accept_resolve(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
+            return ADASPEC_ERR_HIP;
+        return ADASPEC_OK;
+    }
     // the register-resident kernel finds each row's request itself; only the vector kernel needs the plan
     if (!fast && !streaming && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)

@@ -109,7 +109,7 @@ def test_config_attention_vector_path(cfg, oracle_mod, pkg):
 
 @pytest.mark.parametrize("cfg", [3, 5])
 def test_config_accept_register_resident_path(cfg, oracle_mod, pkg):
-    # (AUTO takes the streaming kernel for these two: more logits rows than compute units)
+    # (AUTO takes the two-pass form for these two: more logits rows than compute units)
     st = W.make_verify_step(cfg, attention=False)
     check_accept(st, oracle_mod, pkg, path="fast")
 
@@ -118,6 +118,34 @@ def test_config_accept_register_resident_path(cfg, oracle_mod, pkg):
 def test_config_accept_stream_path(cfg, oracle_mod, pkg):
     st = W.make_verify_step(cfg, attention=False)
     check_accept(st, oracle_mod, pkg, path="stream")
+
+
+@pytest.mark.parametrize("cfg,greedy", [(2, False), (3, False), (4, False), (4, True), (5, False)])
+def test_config_accept_two_pass_path(cfg, greedy, oracle_mod, pkg):
+    """Accept test of every draft row first, then per request the sampling step on the one row that decides
+    its token: same outputs as the per-row kernels, rows after a rejection never read."""
+    st = W.make_verify_step(cfg, greedy=greedy, attention=False)
+    check_accept(st, oracle_mod, pkg, path="two_pass")
+
+
+TWO_PASS_EDGES = [
+    # spec_lens, vocab, dtype, temperatures
+    ([0, 0, 0], 4096, "bf16", [1.0, 0.0, 0.7]),       # no draft row at all: the first pass is not launched
+    ([3, 0, 2], 131072, "bf16", [0.8, 1.0, 0.0]),     # the largest vocabulary of the register-resident kernel
+    ([2, 1], 8, "bf16", [1.0, 0.0]),                  # a single chunk
+    ([5, 0], 8200, "f16", [0.0, 0.9]),                # one chunk into the second step
+    ([7, 7, 1], 32000, "f16", [0.0, 0.0, 0.0]),       # all greedy: rejected rows take the first pass's arg-max
+    ([70, 3], 1024, "bf16", [1.0, 0.9]),              # more drafts than a wavefront has lanes
+]
+
+
+@pytest.mark.parametrize("shape", TWO_PASS_EDGES, ids=lambda s: f"k{s[0]}-V{s[1]}-{s[2]}")
+def test_accept_two_pass_edge_shapes(shape, oracle_mod, pkg):
+    spec, V, dt, T = shape
+    st = W.make_custom_step(4321, ctx_lens=[80] * len(spec), spec_lens=spec, vocab=V, logits_dtype=dt,
+                            temperature=T, attention=False, logits_sigma=3.0, noise_sigma=1.0,
+                            draft_temp=1.1, name=f"two-pass-{dt}")
+    check_accept(st, oracle_mod, pkg, path="two_pass")
 
 
 STREAM_EDGES = [
@@ -258,7 +286,7 @@ def test_accept_stream_p_equals_q_draws_from_target(oracle_mod, pkg):
     st.target_logits[:] = W.f32_to_bf16_bits(np.full(1, 0.25, np.float32))[0]      # p = 1/V exactly
     st.draft_probs[:] = W.f32_to_bf16_bits(np.full(1, 1.0 / V, np.float32))[0]
     st.draft_tokens[:] = rng.integers(0, V, size=B * k)
-    for path in ("stream", "fast"):
+    for path in ("stream", "fast", "two_pass"):
         rep = check_accept(st, oracle_mod, pkg, path=path)
         assert rep["oracle_mean_accept_len"] == k
 
@@ -313,6 +341,7 @@ def test_more_than_1024_requests(oracle_mod, pkg):
     check_attention(st, oracle_mod, pkg)
     check_accept(st, oracle_mod, pkg)
     check_accept(st, oracle_mod, pkg, path="vector")
+    check_accept(st, oracle_mod, pkg, path="two_pass")
 
 
 def test_more_work_items_than_the_plan_keeps_on_chip(oracle_mod, pkg):
@@ -399,7 +428,7 @@ def test_step_replayed_from_a_hip_graph(pkg):
             assert torch.equal(toks, ref_t) and torch.equal(alen, ref_a), (rep, s)
 
 
-@pytest.mark.parametrize("path", ["fast", "stream", "vector"])
+@pytest.mark.parametrize("path", ["fast", "stream", "two_pass", "vector"])
 def test_accept_with_padded_row_strides(path, oracle_mod, pkg):
     """Logits and draft-probability rows that sit in wider buffers (row stride > V)."""
     import torch
