@@ -90,9 +90,16 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
         return v;
     };
 
+    // (the first 1024 draft lengths and temperatures are requested ahead of the row: the memory counter
+    // retires in order, so a value asked for after the row's loads would only be seen once those have landed)
+    int n_first = 0;
+    float t_first = 0.f;
+    if (tid < B) {
+        n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
+        t_first = temperature[tid];
+    }
     // The first kStash steps of the row go straight from memory into the LDS stash (loads that write LDS
-    // need no registers): requested before anything else, they travel while the row's request is being
-    // worked out.  Lane i of a wavefront lands at the wavefront's slot + 16 i, i.e. at stash[step][tid].
+    // need no registers): requested before the row's request is worked out, they travel meanwhile.  Lane i of a wavefront lands at the wavefront's slot + 16 i, i.e. at stash[step][tid].
     {
         const int wvu = __builtin_amdgcn_readfirstlane(wv);
 #pragma unroll
@@ -113,9 +120,13 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
         int carry = 0;
         for (int base = 0; base < B; base += kST) {
             const int i = base + tid;
-            const int n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
-            const float tt = i < B ? temperature[i] : 0.f;
-            const int inc = wave_scan_incl(n, lane);
+            int n = n_first;
+            float tt = t_first;
+            if (base > 0) {
+                n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+                tt = i < B ? temperature[i] : 0.f;
+            }
+            const int inc = wave_scan_incl_dpp(n);
             if (lane == 63) sm.ai[wv] = inc;
             lds_barrier();           // LDS only: the requested steps stay in flight
             int pre = carry, tot = carry;
