@@ -273,7 +273,10 @@ def main() -> int:
                      "frac": gbs(nbytes["attn"], attn_ms) / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": nbytes["attn"], "avg_kernel_ms": attn_ms,
                      "kernel_ms": spread(attn_all)},
-        "roofline_accept": {"bound": "hbm", "kernel": "acceptance main kernel",
+        "roofline_accept": {"bound": "hbm",
+                            "kernel": "acceptance kernels between the library's events (two-pass form: both passes)",
+                            "note": "algorithmic bytes = every logits row and every draft-probability row once; the "
+                                    "two-pass form reads fewer (rows behind a rejection are never read)",
                             "achieved": gbs(nbytes["accept"], acc_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": gbs(nbytes["accept"], acc_ms) / HBM_PEAK_GBS,
                             "algorithmic_bytes": nbytes["accept"], "avg_kernel_ms": acc_ms,
