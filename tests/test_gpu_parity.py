@@ -383,7 +383,8 @@ def test_attention_plan_reuse_across_layers(pkg):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"layer {layer}"
 
 
-def test_step_replayed_from_a_hip_graph(pkg):
+@pytest.mark.parametrize("accept_path", ["auto", "two_pass"])
+def test_step_replayed_from_a_hip_graph(accept_path, pkg):
     """The two calls of a step captured into one HIP graph (the library launches kernels only: no
     allocation, no memset, no synchronisation) and replayed with new inputs in the same buffers; every
     replay must equal the eager result bit for bit, with eager work and synchronisations in between."""
@@ -407,7 +408,8 @@ def test_step_replayed_from_a_hip_graph(pkg):
         pkg.verify_attn(d.q, d.k_pages, d.v_pages, d.block_table, d.ctx_lens, d.spec_lens, o, max_spec_len=kmax,
                         workspace=ws_a, stream=stream)
         pkg.accept(d.target_logits, d.draft_probs, d.draft_tokens, d.uniforms, d.spec_lens, d.temperature,
-                   max_spec_len=kmax, out_tokens=t, out_accept_len=a, workspace=ws_b, stream=stream)
+                   max_spec_len=kmax, out_tokens=t, out_accept_len=a, workspace=ws_b, stream=stream,
+                   path=accept_path)
 
     run(buf, out, toks, alen)                                  # warm-up outside the capture (one-time set-up)
     torch.cuda.synchronize()
