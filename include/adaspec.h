@@ -56,15 +56,14 @@ typedef enum {
 
 typedef enum { ADASPEC_F32 = 0, ADASPEC_F16 = 1, ADASPEC_BF16 = 2 } adaspec_dtype;
 
-/* Kernel selection for adaspec_verify_attn / adaspec_accept.  AUTO picks the
- * matrix-core (attention) / register-resident (accept) kernel when the shape
- * allows and the portable vector kernel otherwise; the other two values force
- * one of them (ADASPEC_ERR_UNSUPPORTED if the shape does not fit it). */
+/* Kernel selection for adaspec_verify_attn / adaspec_accept / adaspec_draft_sample.
+ * AUTO picks the fastest kernel the shape allows (attention: matrix-core, else the
+ * portable vector kernel; acceptance: see adaspec_accept); the other values force
+ * one kernel (ADASPEC_ERR_UNSUPPORTED if the shape does not fit it). */
 typedef enum {
     ADASPEC_PATH_AUTO = 0, ADASPEC_PATH_VECTOR = 1, ADASPEC_PATH_FAST = 2,
     ADASPEC_PATH_STREAM = 3,  /* adaspec_accept only: the streaming 16-bit kernel (V up to 524288), which AUTO
-                                 picks for vocabularies too large for the register-resident kernel and for
-                                 batches with more logits rows than the device has compute units */
+                                 picks for vocabularies too large for the register-resident kernel */
     ADASPEC_PATH_TWO_PASS = 4 /* adaspec_accept only, same shapes as ADASPEC_PATH_FAST: first the accept test
                                  of every draft row (one read of its logits row), then per request the
                                  sampling step on its first rejected row, or on its bonus row, alone.  Rows
