@@ -198,6 +198,15 @@ def main() -> int:
     pkg.set_timing_events(0, None, None)
     pkg.set_timing_events(1, None, None)
     ms_step = (t1 - t0) * 1e3 / args.steps
+    # Which acceptance kernels ran decides what counts as algorithmic bytes: the per-row paths read every
+    # logits row and every sampled draft-probability row; the two-pass path applies the sequential rule
+    # while it works and never reads the rows it skips, so those bytes are not counted for it.
+    accept_path = pkg.accept_resolved_path(dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.spec_lens,
+                                           max_spec_len=kmax, path=args.path)
+    per_row_accept_bytes = nbytes["accept"]
+    if accept_path == "two_pass":
+        skip = W.accept_bytes_skipping_form(st, alen.cpu().numpy())
+        nbytes = dict(nbytes, accept=skip["accept"], total=nbytes["attn"] + skip["accept"])
     # the same rotation replayed from HIP graphs (one captured step per input copy): what a caller that
     # captures its decode loop sees; the library only launches kernels, so the capture needs nothing special
     graphs = []
@@ -265,6 +274,7 @@ def main() -> int:
                    "total_draft_tokens": st.total_draft, "sum_ctx_tokens": int(st.ctx_lens.sum()),
                    "n_q_heads": st.n_q_heads, "n_kv_heads": st.n_kv_heads, "head_dim": st.head_dim,
                    "vocab": st.vocab, "page_size": st.page_size, "kernel_path": args.path,
+                   "accept_kernel_path": accept_path,
                    "step": "1 attention layer + 1 acceptance",
                    "cache": (f"cold: {ncopies} independent input copies in rotation" if ncopies >= 3 else
                              f"WARM: {ncopies} input cop{'y' if ncopies == 1 else 'ies'}, may be served from the memory-side cache")},
@@ -275,8 +285,12 @@ def main() -> int:
                      "kernel_ms": spread(attn_all)},
         "roofline_accept": {"bound": "hbm",
                             "kernel": "acceptance kernels between the library's events (two-pass form: both passes)",
-                            "note": "algorithmic bytes = every logits row and every draft-probability row once; the "
-                                    "two-pass form reads fewer (rows behind a rejection are never read)",
+                            "note": ("two-pass form: algorithmic bytes = every draft row's logits row once (accept "
+                                     "test) + per request the deciding row (with its draft-probability row if it is a "
+                                     "rejected sampled draft); rows the form skips are NOT counted"
+                                     if accept_path == "two_pass" else
+                                     "per-row form: every logits row and every sampled draft-probability row once"),
+                            "per_row_form_bytes": per_row_accept_bytes,
                             "achieved": gbs(nbytes["accept"], acc_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": gbs(nbytes["accept"], acc_ms) / HBM_PEAK_GBS,
                             "algorithmic_bytes": nbytes["accept"], "avg_kernel_ms": acc_ms,

@@ -200,6 +200,14 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const adaspec_accept_dims *dims,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/* The kernel path adaspec_accept takes for these dims and base pointers (the pointers are only
+ * looked at for their alignment): ADASPEC_PATH_VECTOR, _FAST, _STREAM or _TWO_PASS; dims->path
+ * itself unless it is ADASPEC_PATH_AUTO; a negative adaspec_status if dims are invalid or a
+ * forced path does not fit.  Host-only, launches nothing.  For callers that account for the bytes
+ * a call reads: the two-pass path skips rows (see above). */
+int adaspec_accept_resolved_path(const void *target_logits, const void *draft_probs,
+                                 const adaspec_accept_dims *dims);
+
 /* ------------------------------------------------------------------------
  * Optional device-side check of the ragged metadata (for callers that cannot
  * vouch for it): enqueues one small kernel that writes a bit mask to

@@ -23,7 +23,7 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream":
 
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
-    "adaspec_accept_workspace_bytes", "adaspec_accept",
+    "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_resolved_path",
     "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit", "adaspec_draft_sample",
     "adaspec_set_timing_events",
     "adaspec_status_string", "adaspec_version",
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.adaspec_accept_workspace_bytes.argtypes = [C.POINTER(AcceptDims)]
         L.adaspec_accept.restype = C.c_int
         L.adaspec_accept.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
+        L.adaspec_accept_resolved_path.restype = C.c_int
+        L.adaspec_accept_resolved_path.argtypes = [vp, vp, C.POINTER(AcceptDims)]
         L.adaspec_check_ragged_inputs.restype = C.c_int
         L.adaspec_check_ragged_inputs.argtypes = [vp, vp, vp, C.POINTER(AttnDims), vp, vp]
         L.adaspec_kv_append.restype = C.c_int
@@ -202,20 +204,15 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     return out
 
 
-def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, *,
-           max_spec_len: int, out_tokens=None, out_accept_len=None, out_stride: Optional[int] = None,
-           path: str = "auto", workspace=None, stream=None) -> Tuple[object, object]:
-    """adaspec_accept on device tensors; returns (out_tokens [B][out_stride], out_accept_len [B])."""
+def _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path):
+    """(dims, draft_probs pointer, draft_tokens pointer) of an acceptance call: marshalling only."""
     import torch
     TQ, V = target_logits.shape
     B = spec_lens.shape[0]
     TD = TQ - B
     out_stride = int(max_spec_len) + 1 if out_stride is None else int(out_stride)
-    for t in (target_logits, uniforms, spec_lens, temperature):
-        assert t.is_cuda
-    assert target_logits.stride(1) == 1 and uniforms.is_contiguous()
-    assert uniforms.dtype == torch.float32 and temperature.dtype == torch.float32
-    assert spec_lens.dtype == torch.int32
+    assert target_logits.is_cuda and spec_lens.is_cuda
+    assert target_logits.stride(1) == 1 and spec_lens.dtype == torch.int32
     if TD > 0:
         assert draft_probs.shape == (TD, V) and draft_probs.stride(1) == 1
         assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (TD,)
@@ -225,6 +222,29 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
         pdt, pstride, pp, tp = _dtype_code(target_logits), V, None, None
     dims = AcceptDims(B, TQ, TD, int(max_spec_len), V, _dtype_code(target_logits), pdt, out_stride,
                       target_logits.stride(0), pstride, _PATHS[path], 0)
+    return dims, pp, tp
+
+
+def accept_resolved_path(target_logits, draft_probs, draft_tokens, spec_lens, *, max_spec_len: int,
+                         out_stride: Optional[int] = None, path: str = "auto") -> str:
+    """adaspec_accept_resolved_path: the kernel path adaspec_accept takes for these tensors."""
+    dims, pp, _ = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    rc = lib().adaspec_accept_resolved_path(target_logits.data_ptr(), pp, C.byref(dims))
+    if rc < 0:
+        raise AdaspecError(rc, "adaspec_accept_resolved_path")
+    return {v: k for k, v in _PATHS.items()}[rc]
+
+
+def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, *,
+           max_spec_len: int, out_tokens=None, out_accept_len=None, out_stride: Optional[int] = None,
+           path: str = "auto", workspace=None, stream=None) -> Tuple[object, object]:
+    """adaspec_accept on device tensors; returns (out_tokens [B][out_stride], out_accept_len [B])."""
+    import torch
+    for t in (uniforms, temperature):
+        assert t.is_cuda
+    assert uniforms.is_contiguous() and uniforms.dtype == torch.float32 and temperature.dtype == torch.float32
+    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    B, out_stride = dims.batch, dims.out_stride
     if out_tokens is None:
         out_tokens = torch.empty((B, out_stride), dtype=torch.int32, device=target_logits.device)
     if out_accept_len is None:

@@ -180,6 +180,37 @@ size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims)
     return make_accept_plan(*dims).total_bytes;
 }
 
+// The kernel path a call with these dims and pointers takes (an adaspec_path other than AUTO), or a
+// negative status if a forced path does not fit the shape.
+static int resolve_accept_path(const adaspec_accept_dims &d, const void *logits, const void *probs)
+{
+    const bool fast_ok = accept_fast_path_supported(d, logits, probs);
+    const bool stream_ok = accept_stream_path_supported(d, logits, probs);
+    const bool two_pass_ok = fast_ok && stream_ok;
+    if (d.path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
+    if (d.path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
+    if (d.path == ADASPEC_PATH_TWO_PASS && !two_pass_ok) return ADASPEC_ERR_UNSUPPORTED;
+    if (d.path != ADASPEC_PATH_AUTO) return d.path;
+    // AUTO: with at most one logits row per compute unit every row runs at once and a row's own latency is
+    // all there is: the single-pass register-resident kernel is the shortest chain.  With more rows than
+    // compute units the total work counts, and the two-pass form does about half of it (measured on MI355X,
+    // V = 128256: 510 rows 56 us against 60 + 4.6 us for the streaming kernel and the emit kernel; 227 rows
+    // 44 against 35 us).  A row that does not fit the registers of one workgroup (V > 131072) goes to the
+    // streaming kernel, anything else to the vector kernel.
+    if (two_pass_ok && d.total_q > compute_units()) return ADASPEC_PATH_TWO_PASS;
+    if (fast_ok) return ADASPEC_PATH_FAST;
+    if (stream_ok) return ADASPEC_PATH_STREAM;
+    return ADASPEC_PATH_VECTOR;
+}
+
+int adaspec_accept_resolved_path(const void *target_logits, const void *draft_probs,
+                                 const adaspec_accept_dims *dims)
+{
+    const int rc = validate_accept_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    return resolve_accept_path(*dims, target_logits, draft_probs);
+}
+
 int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const int32_t *draft_tokens, const float *uniforms,
                    const int32_t *spec_lens, const float *temperature,
@@ -195,22 +226,10 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
         return ADASPEC_ERR_NULL;
     if (dims->total_draft > 0 && (!draft_probs || !draft_tokens)) return ADASPEC_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
-    const bool fast_ok = accept_fast_path_supported(*dims, target_logits, draft_probs);
-    const bool stream_ok = accept_stream_path_supported(*dims, target_logits, draft_probs);
-    if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
-    if (dims->path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
-    const bool two_pass_ok = fast_ok && stream_ok;
-    if (dims->path == ADASPEC_PATH_TWO_PASS && !two_pass_ok) return ADASPEC_ERR_UNSUPPORTED;
-    // AUTO: with at most one logits row per compute unit every row runs at once and a row's own latency is
-    // all there is: the single-pass register-resident kernel is the shortest chain.  With more rows than
-    // compute units the total work counts, and the two-pass form does about half of it (measured on MI355X,
-    // V = 128256: 510 rows 56 us against 60 + 4.6 us for the streaming kernel and the emit kernel; 227 rows
-    // 44 against 35 us).
-    const bool two_pass = two_pass_ok && (dims->path == ADASPEC_PATH_TWO_PASS ||
-                                          (dims->path == ADASPEC_PATH_AUTO && dims->total_q > compute_units()));
-    // A row that does not fit the registers of one workgroup (V > 131072) goes to the streaming kernel.
-    const bool fast = fast_ok && !two_pass && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_FAST);
-    const bool streaming = !fast && stream_ok && (dims->path == ADASPEC_PATH_AUTO || dims->path == ADASPEC_PATH_STREAM);
+    const int path = resolve_accept_path(*dims, target_logits, draft_probs);
+    if (path < 0) return path;
+    const bool two_pass = path == ADASPEC_PATH_TWO_PASS, fast = path == ADASPEC_PATH_FAST,
+               streaming = path == ADASPEC_PATH_STREAM;
     AcceptArgs a;
     a.plan = make_accept_plan(*dims);
     if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;

@@ -135,6 +135,21 @@ def test_accept_rejects_null_and_small_workspace():
     assert _call_accept(_accept_dims(path=2, vocab=1001, logits_row_stride=1001, probs_row_stride=1001)) == -6
 
 
+def test_accept_resolved_path_of_forced_paths():
+    """The path query is host-only: forced paths come back as they are when the shape fits them, as
+    ADASPEC_ERR_UNSUPPORTED when it does not, and invalid dims as their own status."""
+    L = pkg.lib()
+    q = lambda **kw: L.adaspec_accept_resolved_path(PTR, PTR, C.byref(_accept_dims(**kw)))
+    for path in (1, 2, 3, 4):
+        assert q(path=path) == path
+    assert q(path=2, logits_dtype=F32) == -6 and q(path=4, logits_dtype=F32) == -6 and q(path=3, probs_dtype=F32) == -6
+    big = dict(vocab=262144, logits_row_stride=262144, probs_row_stride=262144)
+    assert q(path=3, **big) == 3 and q(path=2, **big) == -6 and q(path=4, **big) == -6
+    assert L.adaspec_accept_resolved_path(PTR + 8, PTR, C.byref(_accept_dims(path=2))) == -6     # misaligned rows
+    assert q(path=5) == -2 and q(vocab=0) == -2
+    assert L.adaspec_accept_resolved_path(PTR, PTR, None) == -1
+
+
 def test_misc_entry_points_validate():
     L = pkg.lib()
     assert L.adaspec_set_timing_events(3, None, None) == -2

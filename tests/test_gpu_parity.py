@@ -128,6 +128,23 @@ def test_config_accept_two_pass_path(cfg, greedy, oracle_mod, pkg):
     check_accept(st, oracle_mod, pkg, path="two_pass")
 
 
+def test_auto_path_of_the_acceptance(pkg):
+    """AUTO: two-pass with more logits rows than compute units, register-resident with fewer, streaming for
+    vocabularies the registers cannot hold, vector for what none of them takes."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    def resolved(rows, V, dtype=torch.bfloat16, B=4):
+        logits = torch.empty((rows, V), dtype=dtype, device="cuda:0")
+        probs = torch.empty((rows - B, V), dtype=dtype, device="cuda:0")
+        toks = torch.zeros((rows - B,), dtype=torch.int32, device="cuda:0")
+        spec = torch.full((B,), (rows - B) // B, dtype=torch.int32, device="cuda:0")
+        return pkg.accept_resolved_path(logits, probs, toks, spec, max_spec_len=(rows - B) // B)
+    assert resolved(4 * (cus // 4 + 1), 4096) == "two_pass"
+    assert resolved(4 * (cus // 4), 4096) == "fast"
+    assert resolved(8, 151936) == "stream"
+    assert resolved(8, 4096, dtype=torch.float32) == "vector"
+
+
 TWO_PASS_EDGES = [
     # spec_lens, vocab, dtype, temperatures
     ([0, 0, 0], 4096, "bf16", [1.0, 0.0, 0.7]),       # no draft row at all: the first pass is not launched

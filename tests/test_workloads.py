@@ -92,6 +92,20 @@ def test_algorithmic_bytes_formula():
     assert b["total"] == b["attn"] + b["accept"]
 
 
+def test_accept_bytes_of_the_skipping_form():
+    st = W.make_custom_step(6, ctx_lens=[40, 17, 30, 21], spec_lens=[2, 0, 3, 1], vocab=64, logits_dtype="bf16",
+                            temperature=[1.0, 0.5, 0.0, 0.0], attention=False)
+    row = 64 * 2
+    # request 0 rejects its 2nd draft (sampled), 1 has only a bonus row, 2 (greedy) rejects at once, 3 (greedy) accepts
+    b = W.accept_bytes_skipping_form(st, [1, 0, 0, 1])
+    assert b["test_logits"] == 6 * row                     # every draft row once
+    assert b["decide_logits"] == 3 * row                   # requests 0, 1, 3; the rejected greedy one re-reads nothing
+    assert b["decide_probs"] == 1 * row                    # request 0 only
+    assert b["accept"] == 10 * row
+    full = W.algorithmic_bytes(st)["accept"]
+    assert full == 10 * row + 2 * row and b["accept"] <= full
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys, os
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))

@@ -17,4 +17,5 @@ from .verify_step import (  # noqa: F401
     bf16_bits_to_f32,
     to_f64,
     algorithmic_bytes,
+    accept_bytes_skipping_form,
 )

@@ -359,3 +359,22 @@ def algorithmic_bytes(st: VerifyStep) -> Dict[str, int]:
         out["accept"] = out["logits"] + out["probs"]
     out["total"] = out.get("attn", 0) + out.get("accept", 0)
     return out
+
+
+def accept_bytes_skipping_form(st: VerifyStep, accept_len) -> Dict[str, int]:
+    """Bytes of an acceptance that applies the sequential rule while it works (rows behind a
+    request's first rejection are not read, and only the row that decides the request's token is
+    sampled from): every draft row's logits row once for the accept test; then per request the
+    deciding row once more -- with its draft-probability row if it is a rejected sampled draft,
+    not at all if it is a rejected greedy draft (the arg-max of the test is the token).
+    `accept_len[i]` = accepted drafts of request i (the acceptance's own output)."""
+    lsz, psz = _ITEMSIZE[st.logits_dtype], _ITEMSIZE[st.probs_dtype]
+    k = st.spec_lens.astype(np.int64)
+    a = np.asarray(accept_len).astype(np.int64)
+    sampled = st.temperature != 0.0
+    rejected = a < k
+    test = int(k.sum()) * st.vocab * lsz
+    decide_logits = int((sampled | ~rejected).sum()) * st.vocab * lsz
+    decide_probs = int((sampled & rejected).sum()) * st.vocab * psz
+    return {"test_logits": test, "decide_logits": decide_logits, "decide_probs": decide_probs,
+            "accept": test + decide_logits + decide_probs}
