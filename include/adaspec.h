@@ -32,6 +32,10 @@
  *     benchmark).  Calls from several threads are safe as long as they do not
  *     share a workspace.  The calls enqueue kernels only (no allocation, no
  *     memset, no synchronisation), so they can be captured into a HIP graph.
+ *     The first call of a kernel path on a device does its one-time set-up
+ *     (occupancy and device queries; the streaming and two-pass acceptance
+ *     paths also raise their kernel's LDS limit): make one call with the same
+ *     dims outside the capture before capturing.
  */
 #ifndef ADASPEC_H
 #define ADASPEC_H

@@ -163,6 +163,7 @@ def test_accept_two_pass_edge_shapes(shape, oracle_mod, pkg):
                             temperature=T, attention=False, logits_sigma=3.0, noise_sigma=1.0,
                             draft_temp=1.1, name=f"two-pass-{dt}")
     check_accept(st, oracle_mod, pkg, path="two_pass")
+    check_accept(st, oracle_mod, pkg, path="two_pass", out_stride=st.max_spec_len + 3)   # the padding is written too
 
 
 STREAM_EDGES = [
