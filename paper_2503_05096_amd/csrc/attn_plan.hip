@@ -254,23 +254,42 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
     const int64_t idx0 = ((int64_t)s0 * Hkv + g) * max_rows + rr;
     const int64_t step = (int64_t)Hkv * max_rows;                   // from one split's record to the next
     const int c0 = lane * 2;                                         // two adjacent channels per lane and pass
-    float mstar = -INFINITY;
-    for (int s = 0; s < ns; ++s) mstar = fmaxf(mstar, part_ml[(idx0 + s * step) * 2]);
-    float acc[4] = {0.f, 0.f, 0.f, 0.f}, den = 0.f;
-    for (int s = 0; s < ns; ++s) {
-        const int64_t idx = idx0 + s * step;
-        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + idx * 2);
-        const float w = __builtin_amdgcn_exp2f(ml.x - mstar);
-        den += w * ml.y;
+    // Four splits at a time: their (m, l) pairs and partial rows are all requested before any of them is
+    // looked at (one memory round trip per group instead of two per split); groups are merged on line.
+    float mrun = -INFINITY, den = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int sg = 0; sg < ns; sg += 4) {
+        float2 ml[4], o[4][2];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int c = c0 + 128 * e;
-            if (c < d) {
-                const float2 o = *reinterpret_cast<const float2 *>(part_o + idx * d + c);
-                acc[2 * e] += w * o.x;
-                acc[2 * e + 1] += w * o.y;
+        for (int u = 0; u < 4; ++u) {
+            ml[u] = make_float2(-INFINITY, 0.f);
+            o[u][0] = o[u][1] = make_float2(0.f, 0.f);
+            if (sg + u < ns) {
+                const int64_t idx = idx0 + (sg + u) * step;
+                ml[u] = *reinterpret_cast<const float2 *>(part_ml + idx * 2);
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    if (c0 + 128 * e < d) o[u][e] = *reinterpret_cast<const float2 *>(part_o + idx * d + c0 + 128 * e);
             }
         }
+        float gm = mrun;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) gm = fmaxf(gm, ml[u].x);
+        const float keep = __builtin_amdgcn_exp2f(mrun - gm);       // 0 for the first group (mrun = -inf)
+        den *= keep;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] *= keep;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = __builtin_amdgcn_exp2f(ml[u].x - gm);   // 0 for a slot past the last split
+            den += w * ml[u].y;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                acc[2 * e] += w * o[u][e].x;
+                acc[2 * e + 1] += w * o[u][e].y;
+            }
+        }
+        mrun = gm;
     }
     const float inv = 1.0f / den;
 #pragma unroll
