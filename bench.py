@@ -152,7 +152,10 @@ def main() -> int:
     a_dims = pkg.binding.attn_dims(dev.q, dev.k_pages, dev.block_table, max_spec_len=kmax, path=attn_path)
     ws_attn = torch.empty(max(pkg.lib().adaspec_verify_attn_workspace_bytes(C.byref(a_dims)), 256),
                           dtype=torch.uint8, device="cuda:0")
-    ws_acc = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    acc_dims, _, _ = pkg.binding._accept_dims(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.spec_lens,
+                                              kmax, None, args.path)
+    ws_acc = torch.empty(max(pkg.lib().adaspec_accept_workspace_bytes(C.byref(acc_dims)), 256),
+                         dtype=torch.uint8, device="cuda:0")
 
     def step(k=0):
         dv = devs[k % ncopies]

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
     const int32_t *__restrict__ draft_tokens, const float *__restrict__ uniforms,
     const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature, int B, int V,
     int max_spec_len, int64_t lstride, int64_t pstride, int32_t *__restrict__ row_flag,
-    int32_t *__restrict__ row_cand)
+    int32_t *__restrict__ row_cand, RowStat *__restrict__ row_stat)
 {
     using P = Pair16<DT>;
     __shared__ StreamScratch sm;
@@ -255,6 +255,9 @@ __global__ __launch_bounds__(kST, 8) void accept_stream_kernel(
             const float qx = (x & 1) ? P::hi(qw_t) : P::lo(qw_t);
             const float px = __builtin_amdgcn_exp2f(fmaf(lx, c, -mc)) * invZ;
             row_flag[r] = (qx > 0.f) ? (u_t < px / qx) : 1;
+            RowStat st;                       // a rejected row is sampled by the second pass with these
+            st.m = m; st.pad = 0.f; st.Z = Zd;
+            row_stat[r] = st;
         }
         return;
     }
@@ -399,7 +402,8 @@ static hipError_t launch_stream_kernel(const AcceptArgs &a)
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.uniforms,
                            a.spec_lens, a.temperature, d.batch, d.vocab, d.max_spec_len,
                            d.logits_row_stride, d.probs_row_stride,
-                           (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand));
+                           (int32_t *)(a.ws + a.plan.off_row_flag), (int32_t *)(a.ws + a.plan.off_row_cand),
+                           (RowStat *)(a.ws + a.plan.off_row_stat));
     };
     if (d.logits_dtype == ADASPEC_F16) launch(F16{});
     else launch(BF16{});

@@ -120,6 +120,11 @@ AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
     p.off_row_flag = off; off = align_up(off + tq * 4, 256);
     p.off_row_cand = off; off = align_up(off + tq * 4, 256);
     p.off_row_meta = off; off = align_up(off + tq * 32, 256);
+    const size_t nb = (size_t)(d.batch > 0 ? d.batch : 1);
+    p.off_row_stat = off;  off = align_up(off + tq * sizeof(RowStat), 256);
+    p.off_req_pick = off;  off = align_up(off + nb * sizeof(int2), 256);
+    p.off_half_stat = off; off = align_up(off + nb * 2 * sizeof(HalfStat), 256);
+    p.off_part = off;      off = align_up(off + (d.batch <= kSplitMaxBatch ? accept_split_part_bytes((int)nb) : 0), 256);
     p.total_bytes = off;
     return p;
 }
@@ -244,7 +249,9 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
         // decides its token, and the request's outputs (no emit kernel)
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
-        if (launch_accept_test(a) != hipSuccess || launch_accept_resolve(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        const bool split = accept_split_worthwhile(*dims, compute_units());
+        if (launch_accept_test(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        if ((split ? launch_accept_split(a) : launch_accept_resolve(a)) != hipSuccess) return ADASPEC_ERR_HIP;
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
         return ADASPEC_OK;

@@ -420,7 +420,7 @@ def test_step_replayed_from_a_hip_graph(accept_path, pkg):
     toks = torch.empty((st0.batch, kmax + 1), dtype=torch.int32, device="cuda:0")
     alen = torch.empty((st0.batch,), dtype=torch.int32, device="cuda:0")
     ws_a = torch.empty(32 << 20, dtype=torch.uint8, device="cuda:0")
-    ws_b = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    ws_b = torch.empty(4 << 20, dtype=torch.uint8, device="cuda:0")
 
     def run(d, o, t, a, stream=None):
         pkg.verify_attn(d.q, d.k_pages, d.v_pages, d.block_table, d.ctx_lens, d.spec_lens, o, max_spec_len=kmax,
