@@ -1,22 +1,22 @@
-// Two-pass acceptance, second pass for batches of at most half as many requests as the device has
-// compute units: the sampling step on the one row per request that decides its token, cut in two.
+// Two-pass acceptance, second pass for batches of up to 256 requests: the sampling step on the one row
+// per request that decides its token, with the row cut into four parts.
 //
 // A row of V = 128 K elements costs one compute unit about 12 us of vector-ALU time per sweep, and a
-// pass with one workgroup per request leaves the other compute units idle.  So two workgroups share
-// the row (accept_partial_kernel: each adds up the residual mass of its half per (step, wavefront)),
-// and a small kernel per request (accept_pick_kernel) finds the (half, step, wavefront) that holds
+// pass with one workgroup per request is as slow as that one row.  So four workgroups share the row
+// (accept_partial_kernel: each adds up the residual mass of its part per (step, wavefront)), and a
+// small kernel per request (accept_pick_kernel) finds the (part, step, wavefront) that holds
 // tau = u1 * R from those sums, recomputes that one wavefront's 64 chunks and picks the element.
 //
 //   first pass (accept_stream.hip, test-only form): flag of every draft row, (m, Z) of the sampled
 //       draft rows, arg-max of the greedy ones
-//   accept_partial_kernel, workgroup (request i, half h): first row of i (block sum of n), first
+//   accept_partial_kernel, workgroup (request i, part h): first row of i (block sum of n), first
 //       rejected draft a (ballot over the flags) -> deciding row r; h = 0 also writes the accepted
 //       drafts, the padding and the length.  Rejected draft: (m, Z) from the first pass; bonus row:
-//       maximum and normaliser of its own half from registers.  Then per step of 8192 elements
+//       maximum and normaliser of its own part from registers.  Then per step of 8192 elements
 //       r_v = max(0, 2^((l_v - m) c) / Z - q_v) and p_v, summed over 16-lane rows (fp32) and written
 //       as they are: four row sums per (step, wavefront) and kind.
-//   accept_pick_kernel, one workgroup per request: thread (h, step, wavefront) adds its four row
-//       sums in fp64 and puts both halves on one scale (a bonus row's halves have their own (m, Z));
+//   accept_pick_kernel, one workgroup per request: thread (part, step, wavefront) adds its four row
+//       sums in fp64 and puts the parts on one scale (a bonus row's parts have their own (m, Z));
 //       one wavefront scans the steps, then the wavefronts of the step, then the 64 lanes of the
 //       wavefront (same expressions and order as the partial kernel), and the owning lane walks its
 //       8 elements.  R == 0 on a rejected draft (p == q everywhere): the same search on p.
@@ -29,28 +29,30 @@ namespace adaspec {
 
 constexpr int kPT = 1024;                // threads of a partial-sum workgroup
 constexpr int kPW = kPT / kWave;         // its 16 wavefronts
-constexpr int kPSteps = 8;               // steps of 8192 elements per half row (V <= 131072)
-constexpr int kPickT = 256;              // one thread per (half, step, wavefront)
-static_assert(2 * kPSteps * kPW == kPickT, "one pick thread per partial sum");
+constexpr int kRowSteps = 16;            // steps of 8192 elements in the longest row (V <= 131072)
+constexpr int kPickT = kRowSteps * kPW;  // pick kernel: one thread per (part, step, wavefront)
 
-// part: float[B][2 halves][kPSteps][kPW][2 kinds (residual, p)][4 rows of 16 lanes]
+// A row is cut into PARTS parts (2 or 4) of kRowSteps / PARTS steps at most.
+// part: float[B][PARTS][kRowSteps / PARTS][kPW][2 kinds (residual, p)][4 rows of 16 lanes]
+template <int PARTS>
 __device__ __forceinline__ size_t part_index(int i, int h, int it, int w, int kind)
 {
-    return ((((size_t)(i * 2 + h) * kPSteps + it) * kPW + w) * 2 + kind) * 4;
+    return ((((size_t)(i * PARTS + h) * (kRowSteps / PARTS) + it) * kPW + w) * 2 + kind) * 4;
 }
 
-struct HalfGeometry {
-    int half_steps;     // steps of kPT chunks per half
-    int chunk0;         // first 16-byte chunk of the half inside the row
-    int nchunks;        // chunks of the half (0: the row ends before it)
+struct PartGeometry {
+    int part_steps;     // steps of kPT chunks per part
+    int chunk0;         // first 16-byte chunk of the part inside the row
+    int nchunks;        // chunks of the part (0: the row ends before it)
 };
-__device__ __forceinline__ HalfGeometry half_geometry(int V, int h)
+template <int PARTS>
+__device__ __forceinline__ PartGeometry part_geometry(int V, int h)
 {
-    HalfGeometry g;
+    PartGeometry g;
     const int row_chunks = V >> 3, steps = ceil_div(row_chunks, kPT);
-    g.half_steps = (steps + 1) >> 1;
-    g.chunk0 = h * g.half_steps * kPT;
-    g.nchunks = min(max(row_chunks - g.chunk0, 0), g.half_steps * kPT);
+    g.part_steps = ceil_div(steps, PARTS);
+    g.chunk0 = h * g.part_steps * kPT;
+    g.nchunks = min(max(row_chunks - g.chunk0, 0), g.part_steps * kPT);
     return g;
 }
 
@@ -73,8 +75,8 @@ __device__ __forceinline__ void chunk_masses(const uint4 &lv, const uint4 &qv, f
     }
 }
 
-template <class DT>
-__global__ __launch_bounds__(kPT) void accept_partial_kernel(
+template <class DT, int PARTS>
+__global__ __launch_bounds__(kPT, PARTS == 4 ? 8 : 4) void accept_partial_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ spec_lens,
     const float *__restrict__ temperature, int V, int max_spec_len, int64_t lstride, int64_t pstride,
@@ -83,11 +85,12 @@ __global__ __launch_bounds__(kPT) void accept_partial_kernel(
     float *__restrict__ part, HalfStat *__restrict__ half_stat)
 {
     using P = Pair16<DT>;
+    constexpr int kPSteps = kRowSteps / PARTS;
     __shared__ int s_ahead[kPW];
     __shared__ float s_m[kPW], s_z[kPW];
     __shared__ int s_ai[kPW];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int i = blockIdx.x >> 1, h = blockIdx.x & 1;
+    const int i = blockIdx.x / PARTS, h = blockIdx.x % PARTS;
 
     // ---- the request's deciding row (as in the resolve form of accept_fast_kernel) ----------------
     int ahead = 0;
@@ -121,9 +124,9 @@ __global__ __launch_bounds__(kPT) void accept_partial_kernel(
     }
     if (T == 0.0f && !bonus) return;          // greedy and rejected: the first pass left the row's arg-max
 
-    const HalfGeometry g = half_geometry(V, h);
-    float *my_part = part + part_index(i, h, 0, 0, 0);
-    HalfStat *my_stat = half_stat + i * 2 + h;
+    const PartGeometry g = part_geometry<PARTS>(V, h);
+    float *my_part = part + part_index<PARTS>(i, h, 0, 0, 0);
+    HalfStat *my_stat = half_stat + i * PARTS + h;
     auto nothing_here = [&]() {               // the row ends before this half, or the half holds no finite logit
         for (int t = tid; t < kPSteps * kPW * 8; t += kPT) my_part[t] = 0.f;
         if (tid == 0) { HalfStat st; st.m = -INFINITY; st.arg = -1; st.Z = 1.0; *my_stat = st; }
@@ -234,14 +237,14 @@ __global__ __launch_bounds__(kPT) void accept_partial_kernel(
         acc_r = row16_sum(acc_r);
         acc_p = row16_sum(acc_p);
         if ((lane & 15) == 0) {
-            part[part_index(i, h, it, wv, 0) + (lane >> 4)] = acc_r;
-            part[part_index(i, h, it, wv, 1) + (lane >> 4)] = acc_p;
+            part[part_index<PARTS>(i, h, it, wv, 0) + (lane >> 4)] = acc_r;
+            part[part_index<PARTS>(i, h, it, wv, 1) + (lane >> 4)] = acc_p;
         }
     }
     if (tid == 0) { HalfStat st; st.m = m; st.arg = 0; st.Z = Zd; *my_stat = st; }
 }
 
-template <class DT>
+template <class DT, int PARTS>
 __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs, const float *__restrict__ uniforms,
     const int32_t *__restrict__ spec_lens, const float *__restrict__ temperature, int V, int max_spec_len,
@@ -250,7 +253,8 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     const HalfStat *__restrict__ half_stat)
 {
     using P = Pair16<DT>;
-    __shared__ double mass[2][kPSteps][kPW];
+    constexpr int kPSteps = kRowSteps / PARTS;
+    __shared__ double mass[PARTS][kPSteps][kPW];
     __shared__ double s_tau, s_before;
     __shared__ int s_step, s_retry;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -261,15 +265,18 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     const float T = temperature[i];
     const bool bonus = a >= k;
     int32_t *o = out_tokens + (int64_t)i * out_stride + a;
-    const HalfStat st0 = half_stat[i * 2], st1 = half_stat[i * 2 + 1];
+    HalfStat st[PARTS];
+#pragma unroll
+    for (int p = 0; p < PARTS; ++p) st[p] = half_stat[i * PARTS + p];
     if (T == 0.0f) {
         if (tid == 0) {
             int tok = 0;
             if (!bonus) tok = row_cand[r];
             else {
                 ArgMax b{-INFINITY, V};
-                if (st0.arg >= 0) b = ArgMax{st0.m, st0.arg};
-                if (st1.arg >= 0) b = argmax_merge(b, ArgMax{st1.m, st1.arg});
+#pragma unroll
+                for (int p = 0; p < PARTS; ++p)
+                    if (st[p].arg >= 0) b = argmax_merge(b, ArgMax{st[p].m, st[p].arg});
                 tok = b.i < V ? b.i : 0;
             }
             *o = tok;
@@ -277,21 +284,27 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
         return;
     }
 
-    // thread (h, step, wavefront): its residual and probability mass, both halves on one scale
-    const int h = tid >> 7, it = (tid >> 4) & (kPSteps - 1), w = tid & (kPW - 1);
-    const float4 pr = *reinterpret_cast<const float4 *>(part + part_index(i, h, it, w, 0));
-    const float4 pp = *reinterpret_cast<const float4 *>(part + part_index(i, h, it, w, 1));
+    // thread (part, step, wavefront): its residual and probability mass, all parts on one scale
+    const int h = tid / (kPSteps * kPW), it = (tid / kPW) % kPSteps, w = tid % kPW;
+    const float4 pr = *reinterpret_cast<const float4 *>(part + part_index<PARTS>(i, h, it, w, 0));
+    const float4 pp = *reinterpret_cast<const float4 *>(part + part_index<PARTS>(i, h, it, w, 1));
     const float c = 1.4426950408889634f / T;
-    const float M = fmaxf(st0.m, st1.m);
-    // p_v of half h was computed as 2^((l_v - m_h) c) / Z_h: times Z_h 2^((m_h - M) c) it is relative to M in
-    // both halves (a rejected draft row has the same (m, Z) in both: a common factor, which tau absorbs)
-    const double sc0 = st0.m > -INFINITY ? st0.Z * (double)__builtin_amdgcn_exp2f((st0.m - M) * c) : 0.0;
-    const double sc1 = st1.m > -INFINITY ? st1.Z * (double)__builtin_amdgcn_exp2f((st1.m - M) * c) : 0.0;
-    const double my_sc = h ? sc1 : sc0;
+    float M = st[0].m;
+#pragma unroll
+    for (int p = 1; p < PARTS; ++p) M = fmaxf(M, st[p].m);
+    // p_v of part h was computed as 2^((l_v - m_h) c) / Z_h: times Z_h 2^((m_h - M) c) it is relative to M in
+    // every part (a rejected draft row has the same (m, Z) in all: a common factor, which tau absorbs)
+    double sc[PARTS];
+#pragma unroll
+    for (int p = 0; p < PARTS; ++p)
+        sc[p] = st[p].m > -INFINITY ? st[p].Z * (double)__builtin_amdgcn_exp2f((st[p].m - M) * c) : 0.0;
+    double my_sc = sc[0];
+#pragma unroll
+    for (int p = 1; p < PARTS; ++p)
+        if (h == p) my_sc = sc[p];
     const double res = (((double)pr.x + (double)pr.y) + ((double)pr.z + (double)pr.w)) * my_sc;
     const double pm = (((double)pp.x + (double)pp.y) + ((double)pp.z + (double)pp.w)) * my_sc;
-    const HalfGeometry g0 = half_geometry(V, 0);
-    const int steps = ceil_div(V >> 3, kPT), half_steps = g0.half_steps;
+    const int steps = ceil_div(V >> 3, kPT), part_steps = part_geometry<PARTS>(V, 0).part_steps;
     const float u_draw = uniforms[2 * (int64_t)r + 1];
     bool use_p = bonus;                       // (for a bonus row the two sums are the same numbers)
     for (int attempt = 0; attempt < 2; ++attempt) {
@@ -300,7 +313,7 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
         if (wv == 0) {
             // lane L owns step L of the row: total over its wavefronts, running totals over the steps, R,
             // and the step whose running total first exceeds tau
-            const int hh = lane >= half_steps, ii = lane - hh * half_steps;
+            const int hh = lane / part_steps, ii = lane % part_steps;
             double t = 0.0;
             if (lane < steps) {
 #pragma unroll
@@ -324,7 +337,7 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     // ---- inside the step: the wavefront, then the lane, then the element (one wavefront works) -----
     const double tau = s_tau;
     const int sstep = s_step;
-    const int hh = sstep >= half_steps, ii = sstep - hh * half_steps;
+    const int hh = sstep / part_steps, ii = sstep % part_steps;
     const double ws = lane < kPW ? mass[hh][ii][lane] : 0.0;
     const double wincl = s_before + wave_scan_incl(ws, lane);
     const unsigned long long whit = __ballot(lane < kPW && ws > 0.0 && wincl > tau);
@@ -335,9 +348,12 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     }
     const int wstar = whit ? (int)__builtin_ctzll(whit) : 63 - (int)__builtin_clzll(wpos);
     const double base = __shfl(wincl - ws, wstar, kWave);
-    const HalfStat st = hh ? st1 : st0;
-    const double sc = hh ? sc1 : sc0;
-    const int chunk = hh * half_steps * kPT + ii * kPT + wstar * kWave + lane;   // this lane's 16 bytes of the row
+    HalfStat sth = st[0];
+    double sch = sc[0];
+#pragma unroll
+    for (int p = 1; p < PARTS; ++p)
+        if (hh == p) { sth = st[p]; sch = sc[p]; }
+    const int chunk = hh * part_steps * kPT + ii * kPT + wstar * kWave + lane;   // this lane's 16 bytes of the row
     const bool has_q = !bonus && !use_p;
     uint4 lv = make_uint4(P::kNegInf2, P::kNegInf2, P::kNegInf2, P::kNegInf2), qv = make_uint4(0, 0, 0, 0);
     if (chunk < (V >> 3)) {
@@ -345,13 +361,13 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
         if (has_q) qv = *reinterpret_cast<const uint4 *>(probs + (int64_t)(r - i) * pstride * 2 + (int64_t)chunk * 16);
     }
     float rv[8], pv[8], sstar = 0.f;
-    chunk_masses<P>(lv, qv, c, st.m * c, (float)(1.0 / st.Z), rv, pv);   // same expressions as the partial kernel
+    chunk_masses<P>(lv, qv, c, sth.m * c, (float)(1.0 / sth.Z), rv, pv);   // same expressions as the partial kernel
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         if (use_p) rv[e] = pv[e];
         sstar += rv[e];
     }
-    const double mine = (double)sstar * sc;
+    const double mine = (double)sstar * sch;
     const double li = base + wave_scan_incl(mine, lane);
     const unsigned long long lhit = __ballot(sstar > 0.f && li > tau);
     const unsigned long long lpos = __ballot(sstar > 0.f);
@@ -365,7 +381,7 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
         int pick = -1, lastpos = -1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            cum += (double)rv[e] * sc;
+            cum += (double)rv[e] * sch;
             if (rv[e] > 0.f) lastpos = e;
             if (pick < 0 && rv[e] > 0.f && cum > tau) pick = e;
         }
@@ -374,18 +390,20 @@ __global__ __launch_bounds__(kPickT) void accept_pick_kernel(
     }
 }
 
-bool accept_split_worthwhile(const adaspec_accept_dims &d, int compute_units)
-{
-    // two workgroups per request, one per compute unit: only while they all run at once
-    return d.batch <= kSplitMaxBatch && 2 * (int64_t)d.batch <= compute_units;
-}
+// The split second pass keeps 8 KB of partial sums per request: it is set up for batches up to kSplitMaxBatch,
+// larger ones take the pass with one workgroup per request.
+bool accept_split_supported(const adaspec_accept_dims &d) { return d.batch <= kSplitMaxBatch; }
 
-size_t accept_split_part_bytes(int batch) { return (size_t)batch * 2 * kPSteps * kPW * 8 * sizeof(float); }
+size_t accept_split_part_bytes(int batch) { return (size_t)batch * kRowSteps * kPW * 8 * sizeof(float); }
 
 hipError_t launch_accept_split(const AcceptArgs &a)
 {
     const adaspec_accept_dims &d = a.dims;
     if (d.batch == 0) return hipSuccess;
+    // Four parts per row: the partial kernel then stays within 64 registers, two workgroups share a compute
+    // unit, and the four of a request run at once for batches up to half the number of compute units
+    // (measured on MI355X, config 3: 16.7 us against 18.5 us with two parts of 8 steps).
+    constexpr int PARTS = 4;
     auto launch = [&](auto tag) {
         using DT = decltype(tag);
         int32_t *row_flag = (int32_t *)(a.ws + a.plan.off_row_flag), *row_cand = (int32_t *)(a.ws + a.plan.off_row_cand);
@@ -393,11 +411,11 @@ hipError_t launch_accept_split(const AcceptArgs &a)
         int2 *req_pick = (int2 *)(a.ws + a.plan.off_req_pick);
         float *part = (float *)(a.ws + a.plan.off_part);
         HalfStat *half_stat = (HalfStat *)(a.ws + a.plan.off_half_stat);
-        hipLaunchKernelGGL((accept_partial_kernel<DT>), dim3(2 * d.batch), dim3(kPT), 0, a.stream,
+        hipLaunchKernelGGL((accept_partial_kernel<DT, PARTS>), dim3(PARTS * d.batch), dim3(kPT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, a.spec_lens, a.temperature,
                            d.vocab, d.max_spec_len, d.logits_row_stride, d.probs_row_stride, row_flag, row_stat,
                            d.out_stride, a.out_tokens, a.out_accept_len, req_pick, part, half_stat);
-        hipLaunchKernelGGL((accept_pick_kernel<DT>), dim3(d.batch), dim3(kPickT), 0, a.stream,
+        hipLaunchKernelGGL((accept_pick_kernel<DT, PARTS>), dim3(d.batch), dim3(kPickT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.uniforms, a.spec_lens, a.temperature,
                            d.vocab, d.max_spec_len, d.logits_row_stride, d.probs_row_stride, row_cand, d.out_stride,
                            a.out_tokens, req_pick, part, half_stat);

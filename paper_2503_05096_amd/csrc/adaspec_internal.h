@@ -92,8 +92,8 @@ struct AcceptPlan {
     // two-pass form
     size_t off_row_stat;    // RowStat[TQ]: (m, Z) of the sampled draft rows, from the first pass
     size_t off_req_pick;    // int2[B]: (deciding row, accepted drafts) of each request
-    size_t off_half_stat;   // HalfStat[B][2]
-    size_t off_part;        // float[B][2][8][16][2][4]: partial sums of the split second pass (B <= kSplitMaxBatch)
+    size_t off_half_stat;   // HalfStat[B][4]: per part of the row
+    size_t off_part;        // float[B][16 steps][16][2][4]: partial sums of the split second pass (B <= kSplitMaxBatch)
     size_t total_bytes;
 };
 // p_v = 2^((l_v - m) c) / Z of a row (first pass of the two-pass form -> second pass)
@@ -101,7 +101,7 @@ struct RowStat { float m; float pad; double Z; };
 // per (request, half row) of the split second pass: (m, Z) the half's sums are relative to; for a greedy
 // bonus row (maximum, arg-max or -1)
 struct HalfStat { float m; int arg; double Z; };
-// the split second pass runs two workgroups per request and is meant for small batches
+// the split second pass keeps partial sums per request in the workspace: set up for batches up to
 constexpr int kSplitMaxBatch = 256;
 AcceptPlan make_accept_plan(const adaspec_accept_dims &d);
 bool accept_fast_path_supported(const adaspec_accept_dims &d, const void *logits, const void *probs);
@@ -128,9 +128,8 @@ hipError_t launch_accept_stream(const AcceptArgs &a);
 // two-pass form: flags of the draft rows, then one workgroup per request (sampling + outputs)
 hipError_t launch_accept_test(const AcceptArgs &a);
 hipError_t launch_accept_resolve(const AcceptArgs &a);
-// second pass cut in two (two workgroups per request) + the pick kernel, for batches of at most half as
-// many requests as there are compute units
-bool accept_split_worthwhile(const adaspec_accept_dims &d, int compute_units);
+// second pass with the deciding row of each request cut into four parts + the pick kernel (batch <= kSplitMaxBatch)
+bool accept_split_supported(const adaspec_accept_dims &d);
 size_t accept_split_part_bytes(int batch);
 hipError_t launch_accept_split(const AcceptArgs &a);
 

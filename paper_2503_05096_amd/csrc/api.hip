@@ -123,7 +123,7 @@ AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
     const size_t nb = (size_t)(d.batch > 0 ? d.batch : 1);
     p.off_row_stat = off;  off = align_up(off + tq * sizeof(RowStat), 256);
     p.off_req_pick = off;  off = align_up(off + nb * sizeof(int2), 256);
-    p.off_half_stat = off; off = align_up(off + nb * 2 * sizeof(HalfStat), 256);
+    p.off_half_stat = off; off = align_up(off + nb * 4 * sizeof(HalfStat), 256);
     p.off_part = off;      off = align_up(off + (d.batch <= kSplitMaxBatch ? accept_split_part_bytes((int)nb) : 0), 256);
     p.total_bytes = off;
     return p;
@@ -196,13 +196,14 @@ static int resolve_accept_path(const adaspec_accept_dims &d, const void *logits,
     if (d.path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
     if (d.path == ADASPEC_PATH_TWO_PASS && !two_pass_ok) return ADASPEC_ERR_UNSUPPORTED;
     if (d.path != ADASPEC_PATH_AUTO) return d.path;
-    // AUTO: with at most one logits row per compute unit every row runs at once and a row's own latency is
-    // all there is: the single-pass register-resident kernel is the shortest chain.  With more rows than
-    // compute units the total work counts, and the two-pass form does about half of it (measured on MI355X,
-    // V = 128256: 510 rows 56 us against 60 + 4.6 us for the streaming kernel and the emit kernel; 227 rows
-    // 44 against 35 us).  A row that does not fit the registers of one workgroup (V > 131072) goes to the
-    // streaming kernel, anything else to the vector kernel.
-    if (two_pass_ok && d.total_q > compute_units()) return ADASPEC_PATH_TWO_PASS;
+    // AUTO.  The single-pass register-resident kernel is one row's latency: about 20 us at V = 32000, 36 us at
+    // V = 128256 (plus the emit kernel).  The two-pass form does less work per request and spreads the deciding
+    // row over four workgroups, but chains three kernels.  Measured on MI355X: V = 128256, 510 rows 48 against
+    // 60 + 4.6 us (streaming kernel + emit); 227 rows 32 against 36 + 4.3 us (all greedy: 23 against 16 + 4.3 us);
+    // V = 32000, 172 rows 23 against 20 + 4.6 us.  So: two-pass with more rows than compute units (the total
+    // work counts there) and for large vocabularies; a row that does not fit the registers of one workgroup
+    // (V > 131072) goes to the streaming kernel, anything else to the vector kernel.
+    if (two_pass_ok && (d.total_q > compute_units() || d.vocab >= 65536)) return ADASPEC_PATH_TWO_PASS;
     if (fast_ok) return ADASPEC_PATH_FAST;
     if (stream_ok) return ADASPEC_PATH_STREAM;
     return ADASPEC_PATH_VECTOR;
@@ -249,9 +250,9 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
         // decides its token, and the request's outputs (no emit kernel)
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
-        const bool split = accept_split_worthwhile(*dims, compute_units());
         if (launch_accept_test(a) != hipSuccess) return ADASPEC_ERR_HIP;
-        if ((split ? launch_accept_split(a) : launch_accept_resolve(a)) != hipSuccess) return ADASPEC_ERR_HIP;
+        if ((accept_split_supported(*dims) ? launch_accept_split(a) : launch_accept_resolve(a)) != hipSuccess)
+            return ADASPEC_ERR_HIP;
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
         return ADASPEC_OK;

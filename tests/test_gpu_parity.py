@@ -129,8 +129,8 @@ def test_config_accept_two_pass_path(cfg, greedy, oracle_mod, pkg):
 
 
 def test_auto_path_of_the_acceptance(pkg):
-    """AUTO: two-pass with more logits rows than compute units, register-resident with fewer, streaming for
-    vocabularies the registers cannot hold, vector for what none of them takes."""
+    """AUTO: two-pass with more logits rows than compute units or a large vocabulary, register-resident
+    otherwise, streaming for vocabularies the registers cannot hold, vector for what none of them takes."""
     import torch
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     def resolved(rows, V, dtype=torch.bfloat16, B=4):
@@ -141,6 +141,7 @@ def test_auto_path_of_the_acceptance(pkg):
         return pkg.accept_resolved_path(logits, probs, toks, spec, max_spec_len=(rows - B) // B)
     assert resolved(4 * (cus // 4 + 1), 4096) == "two_pass"
     assert resolved(4 * (cus // 4), 4096) == "fast"
+    assert resolved(8, 65536) == "two_pass" and resolved(8, 65528) == "fast"
     assert resolved(8, 151936) == "stream"
     assert resolved(8, 4096, dtype=torch.float32) == "vector"
 
