@@ -167,6 +167,33 @@ def test_accept_two_pass_edge_shapes(shape, oracle_mod, pkg):
     check_accept(st, oracle_mod, pkg, path="two_pass", out_stride=st.max_spec_len + 3)   # the padding is written too
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_accept_two_pass_random_shapes(seed, oracle_mod, pkg):
+    """Random raggedness, vocabulary sizes (whole and ragged numbers of steps and parts), temperatures with a
+    greedy share, both 16-bit types: the two-pass form against the oracle, and against the single-pass kernel
+    where the two must agree exactly (every request whose decision the oracle does not call a near-tie)."""
+    import torch
+    rng = np.random.default_rng(7000 + seed)
+    B = int(rng.integers(1, 40))
+    spec = rng.integers(0, 7, B).astype(np.int32)
+    V = int(rng.choice([8, 1000 * 8, 8192, 8200, 16384 + 8, 24576, 32000, 40960 - 8, 65536]))
+    T = rng.choice(np.array([0.0, 0.6, 1.0, 1.3], np.float32), B, p=[0.2, 0.3, 0.3, 0.2])
+    dt = "bf16" if seed % 2 == 0 else "f16"
+    st = W.make_custom_step(7000 + seed, ctx_lens=[48] * B, spec_lens=spec, vocab=V, logits_dtype=dt, temperature=T,
+                            attention=False, logits_sigma=3.0, noise_sigma=float(rng.choice([0.3, 1.0, 2.0])),
+                            draft_temp=1.1, name=f"two-pass-random-{seed}")
+    rep = check_accept(st, oracle_mod, pkg, path="two_pass")
+    dev = to_device(st, attention=False)
+    kw = dict(max_spec_len=st.max_spec_len)
+    a = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens, dev.temperature,
+                   path="two_pass", **kw)
+    b = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens, dev.temperature,
+                   path="fast", **kw)
+    torch.cuda.synchronize()
+    differ = int((a[0] != b[0]).any(dim=1).sum().item())
+    assert differ <= rep["ratio_near_ties"] + rep["cdf_near_ties"] + 1, (differ, rep)
+
+
 STREAM_EDGES = [
     # spec_lens, vocab, dtype, temperatures
     ([3, 0, 2], 151936, "bf16", [0.8, 1.0, 0.0]),     # beyond the register-resident kernel: AUTO picks the streaming one
