@@ -299,7 +299,10 @@ int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
  *
  * Needs V % 8 == 0, V <= 524288, row strides that are multiples of 8 elements
  * and 16-byte aligned logits / draft_probs (ADASPEC_ERR_UNSUPPORTED or
- * ADASPEC_ERR_ALIGN otherwise).  No workspace.
+ * ADASPEC_ERR_ALIGN otherwise).
+ * Workspace: only the split form uses one (adaspec_draft_sample_workspace_bytes;
+ * 256-byte aligned device memory, contents need not be initialised).  With
+ * workspace == NULL the call runs a single-kernel form.
  * ---------------------------------------------------------------------- */
 typedef struct {
     int32_t rows;               /* R >= 0                                      */
@@ -310,9 +313,18 @@ typedef struct {
     int64_t probs_row_stride;   /* elements between draft_probs rows, >= V     */
     int32_t path;               /* adaspec_path: FAST = register-resident kernel
                                    (16-bit logits, V <= 131072), VECTOR = the
-                                   three-sweep kernel, AUTO = FAST when it fits  */
+                                   three-sweep kernel, TWO_PASS = the split form
+                                   (same shapes as FAST, needs the workspace):
+                                   every row cut into four parts over three small
+                                   kernels, for steps with fewer rows than the
+                                   device has compute units; AUTO = the split
+                                   form when it fits, a workspace is given and
+                                   V >= 32768, else FAST when it fits, else VECTOR */
     int32_t reserved;
 } adaspec_draft_dims;
+
+/* Bytes of workspace the split form needs for these dims (0 if it does not apply). */
+size_t adaspec_draft_sample_workspace_bytes(const adaspec_draft_dims *dims);
 
 int adaspec_draft_sample(const void *draft_logits,      /* [R][V]                               */
                          const float *temperature,      /* [R] >= 0                             */
@@ -321,7 +333,8 @@ int adaspec_draft_sample(const void *draft_logits,      /* [R][V]               
                          void *draft_probs,             /* [max(out_rows)+1][V], written        */
                          int32_t *draft_tokens,         /* [R]                                  */
                          float *confidence,             /* [R]                                  */
-                         const adaspec_draft_dims *dims, void *stream);
+                         const adaspec_draft_dims *dims,
+                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
  * Per-kernel timing for benchmarks: when both events are non-NULL, the next

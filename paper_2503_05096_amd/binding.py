@@ -24,7 +24,8 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream":
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
     "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_resolved_path",
-    "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit", "adaspec_draft_sample",
+    "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
+    "adaspec_draft_sample_workspace_bytes", "adaspec_draft_sample",
     "adaspec_set_timing_events",
     "adaspec_status_string", "adaspec_version",
 )
@@ -98,7 +99,9 @@ def lib() -> C.CDLL:
         L.adaspec_commit.restype = C.c_int
         L.adaspec_commit.argtypes = [vp] * 10 + [C.POINTER(CommitDims), vp]
         L.adaspec_draft_sample.restype = C.c_int
-        L.adaspec_draft_sample.argtypes = [vp] * 7 + [C.POINTER(DraftDims), vp]
+        L.adaspec_draft_sample.argtypes = [vp] * 7 + [C.POINTER(DraftDims), vp, C.c_size_t, vp]
+        L.adaspec_draft_sample_workspace_bytes.restype = C.c_size_t
+        L.adaspec_draft_sample_workspace_bytes.argtypes = [C.POINTER(DraftDims)]
         L.adaspec_set_timing_events.restype = C.c_int
         L.adaspec_set_timing_events.argtypes = [C.c_int, vp, vp]
         L.adaspec_status_string.restype = C.c_char_p
@@ -325,8 +328,9 @@ def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, *, max_spec_len: int
 
 
 def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft_probs=None, out_rows=None,
-                 draft_tokens=None, confidence=None, path: str = "auto", stream=None):
-    """adaspec_draft_sample; returns (draft_probs, draft_tokens [R] int32, confidence [R] float32)."""
+                 draft_tokens=None, confidence=None, path: str = "auto", workspace=None, stream=None):
+    """adaspec_draft_sample; returns (draft_probs, draft_tokens [R] int32, confidence [R] float32).
+    path "split" (ADASPEC_PATH_TWO_PASS for this call) cuts every row into four parts."""
     import torch
     R, V = draft_logits.shape
     dev = draft_logits.device
@@ -341,11 +345,15 @@ def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft
     if confidence is None:
         confidence = torch.empty((R,), dtype=torch.float32, device=dev)
     dims = DraftDims(R, V, _dtype_code(draft_logits), _dtype_code(draft_probs), draft_logits.stride(0),
-                     draft_probs.stride(0), _PATHS[path], 0)
-    rc = lib().adaspec_draft_sample(draft_logits.data_ptr(), temperature.data_ptr(), uniforms.data_ptr(),
-                                    None if out_rows is None else out_rows.data_ptr(), draft_probs.data_ptr(),
-                                    draft_tokens.data_ptr(), confidence.data_ptr(), C.byref(dims),
-                                    _stream_ptr(stream))
+                     draft_probs.stride(0), PATH_TWO_PASS if path == "split" else _PATHS[path], 0)
+    L = lib()
+    need = L.adaspec_draft_sample_workspace_bytes(C.byref(dims))
+    ws = _workspace(need, dev, workspace) if need else None
+    rc = L.adaspec_draft_sample(draft_logits.data_ptr(), temperature.data_ptr(), uniforms.data_ptr(),
+                                None if out_rows is None else out_rows.data_ptr(), draft_probs.data_ptr(),
+                                draft_tokens.data_ptr(), confidence.data_ptr(), C.byref(dims),
+                                None if ws is None else ws.data_ptr(), 0 if ws is None else ws.numel(),
+                                _stream_ptr(stream))
     if rc != 0:
         raise AdaspecError(rc, "adaspec_draft_sample")
     return draft_probs, draft_tokens, confidence

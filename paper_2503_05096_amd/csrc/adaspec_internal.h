@@ -142,6 +142,12 @@ hipError_t launch_draft_sample(const void *logits, const float *temperature, con
                                const int32_t *out_rows, void *probs, int32_t *tokens, float *confidence,
                                const adaspec_draft_dims &d, hipStream_t stream);
 bool draft_fast_supported(const adaspec_draft_dims &d);
+// every row cut into four parts, three kernels (draft_split.hip); ws = draft_split_workspace_bytes(rows)
+bool draft_split_supported(const adaspec_draft_dims &d);
+size_t draft_split_workspace_bytes(int rows);
+hipError_t launch_draft_split(const void *logits, const float *temperature, const float *uniforms,
+                              const int32_t *out_rows, void *probs, int32_t *tokens, float *confidence,
+                              const adaspec_draft_dims &d, char *ws, hipStream_t stream);
 hipError_t launch_draft_fast(const void *logits, const float *temperature, const float *uniforms,
                              const int32_t *out_rows, void *probs, int32_t *tokens, float *confidence,
                              const adaspec_draft_dims &d, hipStream_t stream);

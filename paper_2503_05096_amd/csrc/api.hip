@@ -326,33 +326,66 @@ int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
     return ADASPEC_OK;
 }
 
-int adaspec_draft_sample(const void *draft_logits, const float *temperature, const float *uniforms,
-                         const int32_t *out_rows, void *draft_probs, int32_t *draft_tokens,
-                         float *confidence, const adaspec_draft_dims *d, void *stream)
+static int validate_draft_dims(const adaspec_draft_dims *d)
 {
     if (!d) return ADASPEC_ERR_NULL;
     if (d->rows < 0 || d->vocab <= 0) return ADASPEC_ERR_DIM;
     if (d->logits_row_stride < d->vocab || d->probs_row_stride < d->vocab) return ADASPEC_ERR_DIM;
     if (!dtype_ok(d->logits_dtype) || !dtype_ok(d->probs_dtype)) return ADASPEC_ERR_DTYPE;
+    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_TWO_PASS || d->path == ADASPEC_PATH_STREAM)
+        return ADASPEC_ERR_DIM;
+    return ADASPEC_OK;
+}
+
+size_t adaspec_draft_sample_workspace_bytes(const adaspec_draft_dims *d)
+{
+    if (validate_draft_dims(d) != ADASPEC_OK || d->rows == 0) return 0;
+    if (d->vocab % 8 || d->logits_row_stride % 8 || d->probs_row_stride % 8 || !draft_split_supported(*d)) return 0;
+    if (d->path == ADASPEC_PATH_VECTOR || d->path == ADASPEC_PATH_FAST) return 0;
+    return draft_split_workspace_bytes(d->rows);
+}
+
+int adaspec_draft_sample(const void *draft_logits, const float *temperature, const float *uniforms,
+                         const int32_t *out_rows, void *draft_probs, int32_t *draft_tokens,
+                         float *confidence, const adaspec_draft_dims *d, void *workspace, size_t workspace_bytes,
+                         void *stream)
+{
+    const int rc = validate_draft_dims(d);
+    if (rc != ADASPEC_OK) return rc;
     if (d->rows == 0) return ADASPEC_OK;
     if (!draft_logits || !temperature || !uniforms || !draft_probs || !draft_tokens || !confidence)
         return ADASPEC_ERR_NULL;
     if (!aligned16(draft_logits) || !aligned16(draft_probs)) return ADASPEC_ERR_ALIGN;
     if (!draft_sample_supported(*d, draft_logits, draft_probs)) return ADASPEC_ERR_UNSUPPORTED;
-    if (d->path < ADASPEC_PATH_AUTO || d->path > ADASPEC_PATH_FAST) return ADASPEC_ERR_DIM;
     const bool fast_ok = draft_fast_supported(*d);
+    const bool split_ok = draft_split_supported(*d);
     if (d->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
-    const bool fast = fast_ok && d->path != ADASPEC_PATH_VECTOR;
-    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_start[2], static_cast<hipStream_t>(stream)) != hipSuccess)
-        return ADASPEC_ERR_HIP;
-    const hipError_t e = fast
-        ? launch_draft_fast(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
-                            confidence, *d, static_cast<hipStream_t>(stream))
-        : launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens,
-                              confidence, *d, static_cast<hipStream_t>(stream));
+    bool split = false;
+    if (d->path == ADASPEC_PATH_TWO_PASS) {
+        if (!split_ok) return ADASPEC_ERR_UNSUPPORTED;
+        if (!workspace) return ADASPEC_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
+        if (workspace_bytes < draft_split_workspace_bytes(d->rows)) return ADASPEC_ERR_WORKSPACE;
+        split = true;
+    } else if (d->path == ADASPEC_PATH_AUTO) {
+        // three small kernels against one long one: worth it once a row is long (measured on MI355X, 128 rows:
+        // V = 128256 24 against 36 us)
+        split = split_ok && d->vocab >= 32768 && workspace && !(reinterpret_cast<uintptr_t>(workspace) & 255u) &&
+                workspace_bytes >= draft_split_workspace_bytes(d->rows);
+    }
+    const bool fast = !split && fast_ok && d->path != ADASPEC_PATH_VECTOR;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_start[2], st) != hipSuccess) return ADASPEC_ERR_HIP;
+    hipError_t e;
+    if (split)
+        e = launch_draft_split(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens, confidence, *d,
+                               static_cast<char *>(workspace), st);
+    else if (fast)
+        e = launch_draft_fast(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens, confidence, *d, st);
+    else
+        e = launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens, confidence, *d, st);
     if (e != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_stop[2], static_cast<hipStream_t>(stream)) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_stop[2], st) != hipSuccess) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
 

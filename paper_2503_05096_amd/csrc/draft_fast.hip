@@ -16,6 +16,7 @@
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"
+#include "draft_common.h"
 
 namespace adaspec {
 
@@ -31,34 +32,6 @@ struct DraftFastScratch {
     int    sstar;
     int    first_hit, last_pos;
 };
-
-// the 8 probabilities of one chunk: computed in fp32, rounded once to the storage type PT;
-// returns them as floats (the rounded values) and, for 16-bit storage, packed for the store
-template <class DT, class PT>
-__device__ __forceinline__ void chunk_probs(const uint4 &lg, float c2, float mc, float invZ, float (&q)[8], uint4 &packed)
-{
-    using P = Pair16<DT>;
-    const uint32_t w[4] = {lg.x, lg.y, lg.z, lg.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        float a = __builtin_amdgcn_exp2f(fmaf(P::lo(w[e]), c2, -mc)) * invZ;
-        float b = __builtin_amdgcn_exp2f(fmaf(P::hi(w[e]), c2, -mc)) * invZ;
-        if constexpr (std::is_same<PT, BF16>::value) {
-            const uint16_t ba = float_to_bf16_bits(a), bb = float_to_bf16_bits(b);
-            a = bf16_bits_to_float(ba); b = bf16_bits_to_float(bb);
-            o[e] = (uint32_t)ba | ((uint32_t)bb << 16);
-        } else if constexpr (std::is_same<PT, F16>::value) {
-            const uint16_t ba = float_to_f16_bits(a), bb = float_to_f16_bits(b);
-            a = f16_bits_to_float(ba); b = f16_bits_to_float(bb);
-            o[e] = (uint32_t)ba | ((uint32_t)bb << 16);
-        } else {
-            o[e] = 0;
-        }
-        q[2 * e] = a; q[2 * e + 1] = b;
-    }
-    packed = make_uint4(o[0], o[1], o[2], o[3]);
-}
 
 template <class DT, class PT, int ITER>
 __global__ __launch_bounds__(kGT) void draft_fast_kernel(
@@ -190,16 +163,20 @@ __global__ __launch_bounds__(kGT) void draft_fast_kernel(
         float q[8];
         uint4 packed;
         chunk_probs<DT, PT>(lg[it], c2, mc, invZ, q, packed);
+        // (The step's offset goes into the lane offset, not into the scalar-offset operand: with a scalar
+        // register there the compiler leaves no wait state between a 16-byte buffer store and a vector
+        // instruction that overwrites its data registers, and on gfx950 the store was seen to pick up the
+        // new value of its first data register.)
         if constexpr (kPsz == 2) {
-            __builtin_amdgcn_raw_buffer_store_b128(u32x4{packed.x, packed.y, packed.z, packed.w}, rp, (int)tid16,
-                                                   it * (kGT * 16), 0);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{packed.x, packed.y, packed.z, packed.w}, rp,
+                                                   (int)tid16 + it * (kGT * 16), 0, 0);
         } else {
             __builtin_amdgcn_raw_buffer_store_b128(
                 u32x4{__float_as_uint(q[0]), __float_as_uint(q[1]), __float_as_uint(q[2]), __float_as_uint(q[3])}, rp,
-                (int)(tid16 * 2), it * (kGT * 32), 0);
+                (int)(tid16 * 2) + it * (kGT * 32), 0, 0);
             __builtin_amdgcn_raw_buffer_store_b128(
                 u32x4{__float_as_uint(q[4]), __float_as_uint(q[5]), __float_as_uint(q[6]), __float_as_uint(q[7])}, rp,
-                (int)(tid16 * 2 + 16), it * (kGT * 32), 0);
+                (int)(tid16 * 2 + 16) + it * (kGT * 32), 0, 0);
         }
         float acc = 0.f;
 #pragma unroll

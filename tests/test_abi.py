@@ -189,19 +189,30 @@ def test_draft_sample_validates():
     L = pkg.lib()
     ok = DraftDims(4, 1024, BF16, BF16, 1024, 1024, 0, 0)
     args = [PTR, PTR, PTR, None, PTR, PTR, PTR]
-    assert L.adaspec_draft_sample(*args, None, None) == -1
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(-1, 1024, BF16, BF16, 1024, 1024, 0, 0)), None) == -2
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1000, 1024, 0, 0)), None) == -2
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, 9, BF16, 1024, 1024, 0, 0)), None) == -3
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1001, BF16, BF16, 1001, 1001, 0, 0)), None) == -6
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1028, 1024, 0, 0)), None) == -6
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, F32, BF16, 1024, 1024, 2, 0)), None) == -6   # fast path needs 16-bit logits
-    assert L.adaspec_draft_sample(*args, C.byref(DraftDims(4, 1024, BF16, BF16, 1024, 1024, 5, 0)), None) == -2
+    call = lambda a, d, ws=None, nb=0: L.adaspec_draft_sample(*a, None if d is None else C.byref(d), ws, nb, None)
+    assert call(args, None) == -1
+    assert call(args, DraftDims(-1, 1024, BF16, BF16, 1024, 1024, 0, 0)) == -2
+    assert call(args, DraftDims(4, 1024, BF16, BF16, 1000, 1024, 0, 0)) == -2
+    assert call(args, DraftDims(4, 1024, 9, BF16, 1024, 1024, 0, 0)) == -3
+    assert call(args, DraftDims(4, 1001, BF16, BF16, 1001, 1001, 0, 0)) == -6
+    assert call(args, DraftDims(4, 1024, BF16, BF16, 1028, 1024, 0, 0)) == -6
+    assert call(args, DraftDims(4, 1024, F32, BF16, 1024, 1024, 2, 0)) == -6   # fast path needs 16-bit logits
+    assert call(args, DraftDims(4, 1024, BF16, BF16, 1024, 1024, 5, 0)) == -2
+    assert call(args, DraftDims(4, 1024, BF16, BF16, 1024, 1024, 3, 0)) == -2  # the streaming path is the acceptance's
     bad = list(args); bad[0] = None
-    assert L.adaspec_draft_sample(*bad, C.byref(ok), None) == -1
+    assert call(bad, ok) == -1
     mis = list(args); mis[4] = PTR + 8
-    assert L.adaspec_draft_sample(*mis, C.byref(ok), None) == -4
-    assert L.adaspec_draft_sample(*[None] * 7, C.byref(DraftDims(0, 1024, BF16, BF16, 1024, 1024, 0, 0)), None) == 0
+    assert call(mis, ok) == -4
+    # the split form: needs its workspace, 256-byte aligned and large enough; not for fp32 logits
+    split = DraftDims(4, 1024, BF16, BF16, 1024, 1024, 4, 0)
+    need = L.adaspec_draft_sample_workspace_bytes(C.byref(split))
+    assert need > 0 and L.adaspec_draft_sample_workspace_bytes(C.byref(ok)) == need
+    assert L.adaspec_draft_sample_workspace_bytes(C.byref(DraftDims(4, 1024, BF16, BF16, 1024, 1024, 2, 0))) == 0
+    assert L.adaspec_draft_sample_workspace_bytes(C.byref(DraftDims(4, 1024, F32, BF16, 1024, 1024, 0, 0))) == 0
+    assert L.adaspec_draft_sample_workspace_bytes(None) == 0
+    assert call(args, split) == -1 and call(args, split, PTR + 16, need) == -4 and call(args, split, PTR, need - 1) == -5
+    assert call(args, DraftDims(4, 1024, F32, BF16, 1024, 1024, 4, 0), PTR, need) == -6
+    assert call([None] * 7, DraftDims(0, 1024, BF16, BF16, 1024, 1024, 0, 0)) == 0
 
 
 def test_one_hip_runtime_whatever_the_import_order():

@@ -102,6 +102,7 @@ def test_draft_sample_on_config_logits(cfg, oracle_mod, pkg):
         _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg)
     else:
         _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg, path="fast")
+        _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg, path="split")
         _check(logits, st.logits_dtype, st.probs_dtype, T, u, oracle_mod, pkg, path="vector")
 
 
@@ -114,16 +115,18 @@ def test_draft_sample_dtype_mixes_strides_and_row_map(oracle_mod, pkg):
     u[0], u[3] = 0.0, np.float32(1.0 - 2.0 ** -24)                    # the ends of the range
     for ldt, pdt in [("f32", "f32"), ("f32", "bf16"), ("bf16", "f16"), ("f16", "bf16")]:
         lg = base if ldt == "f32" else (W.f32_to_bf16_bits(base) if ldt == "bf16" else base.astype(np.float16))
-        for path in (["vector"] if ldt == "f32" else ["fast", "vector"]):
+        for path in (["vector"] if ldt == "f32" else ["fast", "split", "vector"]):
             _check(lg, ldt, pdt, T, u, oracle_mod, pkg, path=path)
     _check(W.f32_to_bf16_bits(base), "bf16", "f32", T, u, oracle_mod, pkg, path="fast")
+    _check(W.f32_to_bf16_bits(base), "bf16", "f32", T, u, oracle_mod, pkg, path="split")
     # scattered destination rows (the ragged layout the acceptance call reads)
     out_rows = np.array([3, 0, 11, 4, 5, 9, 1, 12, 7], np.int32)
-    for path in ("fast", "vector"):
+    for path in ("fast", "split", "vector"):
         _check(W.f32_to_bf16_bits(base), "bf16", "bf16", T, u, oracle_mod, pkg, out_rows=out_rows, n_prob_rows=13, path=path)
     # a row with no positive logit takes the exact-maximum branch of the register-resident kernel
     neg = W.f32_to_bf16_bits(-np.abs(base[:3]) - 0.5)
     _check(neg, "bf16", "bf16", T[:3], u[:3], oracle_mod, pkg, path="fast")
+    _check(neg, "bf16", "bf16", T[:3], u[:3], oracle_mod, pkg, path="split")
 
 
 def test_draft_sample_small_vocab_and_planted_ties(oracle_mod, pkg):
@@ -133,7 +136,11 @@ def test_draft_sample_small_vocab_and_planted_ties(oracle_mod, pkg):
     lg[1, [2, 6]] = 5.0                                               # tie for the maximum
     lg[4, :] = 0.25                                                   # all equal
     T = np.array([1.0, 0.0, 0.3, 1.0, 0.0, 1.0], np.float32)
-    _check(lg, "f32", "f32", T, rng.random(R).astype(np.float32), oracle_mod, pkg)
+    u = rng.random(R).astype(np.float32)
+    _check(lg, "f32", "f32", T, u, oracle_mod, pkg)
+    # one chunk only: three of the four parts of the split form are empty
+    _check(W.f32_to_bf16_bits(lg), "bf16", "bf16", T, u, oracle_mod, pkg, path="split")
+    _check(lg.astype(np.float16), "f16", "f16", T, u, oracle_mod, pkg, path="split")
 
 
 def test_draft_then_accept_roundtrip(oracle_mod, pkg):
