@@ -66,3 +66,30 @@ def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, next_spec_lens=None,
                     st[i, sl[i]] = out_tokens[i, t]
                     sl[i] += 1
     return dict(committed_lens=committed, next_ctx_lens=nxt, last_token=last, seq_tokens=st, seq_lens=sl)
+
+
+def kv_compact_path(k_pages, v_pages, block_table, ctx_lens, spec_lens, out_path, out_accept_len):
+    """After TREE acceptance: returns copies of (k_pages, v_pages) in which the K/V rows of the
+    accepted nodes sit where a chain would have put them.
+
+    The n_i = k_i + 1 nodes of request i were appended at positions base + j, base = L_i - n_i,
+    in node order.  The walk accepted the nodes out_path[i][0 .. a_i-1] (a root-to-node path, so
+    strictly increasing and out_path[i][j] >= j + 1).  Afterwards position base + 1 + j holds the
+    row of node out_path[i][j]; the root stays at base; positions from base + 1 + a_i on are dead
+    (whatever they hold is never read again once `commit` has shortened the request)."""
+    kp, vp = k_pages.copy(), v_pages.copy()
+    P = kp.shape[2]
+    for i in range(len(spec_lens)):
+        n, a = int(spec_lens[i]) + 1, int(out_accept_len[i])
+        base = int(ctx_lens[i]) - n
+        prev = 0
+        for j in range(a):
+            node = int(out_path[i, j])
+            assert prev < node < n and node >= j + 1
+            prev = node
+            src, dst = base + node, base + 1 + j
+            ps, pd = int(block_table[i, src // P]), int(block_table[i, dst // P])
+            # taken from the ORIGINAL pages: a destination never overwrites a source still needed
+            kp[pd, :, dst % P, :] = k_pages[ps, :, src % P, :]
+            vp[pd, :, dst % P, :] = v_pages[ps, :, src % P, :]
+    return kp, vp

@@ -121,3 +121,60 @@ def test_commit_identities_on_a_config(oracle_mod):
     assert np.array_equal(r["last_token"], toks[np.arange(st.batch), alen])
     assert np.all(r["last_token"] >= 0)
     assert r["next_ctx_lens"] is None and r["seq_tokens"] is None
+
+
+# ------------------------------------------------------------ tree: compaction of the accepted path
+def test_compact_path_hand_example():
+    # one request, P = 4, base = 2, nodes 0..4 at positions 2..6; accepted path = nodes 2, 4
+    P, d = 4, 1
+    kp = np.arange(3 * P, dtype=np.float32).reshape(3, 1, P, d)      # page p, slot s holds 4p + s
+    vp = 100 + kp
+    bt = np.array([[2, 0]], np.int32)                                 # positions 0..3 -> page 2, 4..7 -> page 0
+    ctx, spec = np.array([7], np.int32), np.array([4], np.int32)
+    path = np.array([[2, 4, -1, -1, -1]], np.int32)
+    k2, v2 = KV.kv_compact_path(kp, vp, bt, ctx, spec, path, np.array([2], np.int32))
+    # node 2 sat at position 4 (page 0, slot 0, value 0) -> position 3 (page 2, slot 3)
+    # node 4 sat at position 6 (page 0, slot 2, value 2) -> position 4 (page 0, slot 0)
+    assert k2[2, 0, 3, 0] == 0 and k2[0, 0, 0, 0] == 2 and v2[2, 0, 3, 0] == 100 and v2[0, 0, 0, 0] == 102
+    changed = (k2 != kp)
+    assert changed.sum() == 2                                         # nothing else moved
+
+
+def test_compact_path_properties():
+    rng = np.random.default_rng(4)
+    spec = np.array([0, 5, 9, 3, 16], np.int32)
+    st = W.make_custom_step(9, ctx_lens=[1, 20, 33, 4, 50], spec_lens=spec, n_q_heads=2, n_kv_heads=2,
+                            head_dim=8, dtype="f32", acceptance=False, poison=False)
+    W.attach_tree(st, max_width=3)
+    cu = st.cu_q
+    B = st.batch
+    path = -np.ones((B, int(spec.max()) + 1), np.int32)
+    alen = np.zeros(B, np.int32)
+    for i in range(B):                                                # a random root-to-node path
+        par = st.parents[cu[i]:cu[i + 1]]
+        u, walk = 0, []
+        while True:
+            kids = [c for c in range(u + 1, spec[i] + 1) if par[c] == u]
+            if not kids or rng.random() < 0.2:
+                break
+            u = int(rng.choice(kids))
+            walk.append(u)
+        path[i, :len(walk)] = walk
+        alen[i] = len(walk)
+    assert alen.max() >= 2
+    k2, v2 = KV.kv_compact_path(st.k_pages, st.v_pages, st.block_table, st.ctx_lens, spec, path, alen)
+    for i in range(B):
+        base = int(st.ctx_lens[i]) - int(spec[i]) - 1
+        for pos in range(base + 1):                                   # committed context and root untouched
+            assert np.array_equal(_gather(k2, st.block_table, i, pos), _gather(st.k_pages, st.block_table, i, pos))
+        for j in range(alen[i]):
+            assert np.array_equal(_gather(k2, st.block_table, i, base + 1 + j),
+                                  _gather(st.k_pages, st.block_table, i, base + path[i, j]))
+            assert np.array_equal(_gather(v2, st.block_table, i, base + 1 + j),
+                                  _gather(st.v_pages, st.block_table, i, base + path[i, j]))
+    # a chain's path is 1, 2, ...: nothing moves
+    W.attach_tree(st, chain=True)
+    chain_path = np.where(np.arange(path.shape[1])[None] < alen[:, None], np.arange(1, path.shape[1] + 1)[None], -1)
+    k3, v3 = KV.kv_compact_path(st.k_pages, st.v_pages, st.block_table, st.ctx_lens, spec,
+                                chain_path.astype(np.int32), alen)
+    assert np.array_equal(k3, st.k_pages) and np.array_equal(v3, st.v_pages)

@@ -111,3 +111,36 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_attach_tree_structure_and_determinism():
+    st = W.make_custom_step(31, ctx_lens=[40, 9, 20, 64], spec_lens=[12, 0, 5, 30], vocab=32, attention=False,
+                            temperature=[1.0, 1.0, 0.0, 0.8])
+    chain_tokens = st.draft_tokens.copy()
+    W.attach_tree(st, max_width=3)
+    again = W.attach_tree(W.make_custom_step(31, ctx_lens=[40, 9, 20, 64], spec_lens=[12, 0, 5, 30], vocab=32,
+                                             attention=False, temperature=[1.0, 1.0, 0.0, 0.8]), max_width=3)
+    assert np.array_equal(st.parents, again.parents) and np.array_equal(st.draft_tokens, again.draft_tokens)
+    assert st.parents.shape == (st.total_q,) and st.draft_tokens.shape == chain_tokens.shape
+    cu = st.cu_q
+    for i in range(st.batch):
+        par = st.parents[cu[i]:cu[i + 1]]
+        assert par[0] == -1 and all(0 <= par[c] < c for c in range(1, len(par)))     # parents come first
+        if len(par) > 1:
+            assert np.bincount(par[1:]).max() <= 3
+        # a token handed out by the generator has mass in its parent's draft distribution
+        for c in range(1, len(par)):
+            q = W.to_f64(st.draft_probs[cu[i] - i + par[c]], st.probs_dtype)
+            assert q[st.draft_tokens[cu[i] - i + c - 1]] > 0
+    # greedy request: siblings are the distinct top tokens of the parent's row, best first
+    i = 2
+    par = st.parents[cu[i]:cu[i + 1]]
+    for u in range(len(par)):
+        kids = [c for c in range(1, len(par)) if par[c] == u]
+        if kids:
+            q = W.to_f64(st.draft_probs[cu[i] - i + u], st.probs_dtype)
+            assert [st.draft_tokens[cu[i] - i + c - 1] for c in kids] == list(np.argsort(-q, kind="stable")[:len(kids)])
+    assert max(np.bincount(st.parents[st.parents >= 0]).max(), 0) >= 2                # some node branches
+    W.attach_tree(st, chain=True)
+    for i in range(st.batch):
+        assert list(st.parents[cu[i]:cu[i + 1]]) == list(range(-1, int(st.spec_lens[i])))

@@ -121,6 +121,7 @@ class VerifyStep:
     draft_tokens: np.ndarray = None   # int32 [TD]
     uniforms: np.ndarray = None       # float32 [TQ][2]
     temperature: np.ndarray = None    # float32 [B]
+    parents: np.ndarray = None        # int32 [TQ], only for draft TREES: parent node inside the request
     notes: Dict[str, object] = field(default_factory=dict)
 
     @property
@@ -334,6 +335,54 @@ def make_custom_step(seed: int, ctx_lens, spec_lens, *, n_q_heads=8, n_kv_heads=
                   n_kv_heads=n_kv_heads, head_dim=head_dim, dtype=dtype, vocab=vocab,
                   logits_dtype=logits_dtype, logits_sigma=logits_sigma,
                   noise_sigma=noise_sigma, draft_temp=draft_temp, **kw)
+
+
+def attach_tree(st: VerifyStep, max_width: int = 3, seed: Optional[int] = None,
+                chain: bool = False) -> VerifyStep:
+    """Turn the drafts of every request into a token TREE (in place; returns `st`).
+
+    Node 0 of a request is its root (the last committed token), nodes 1..k_i its drafts; a
+    node's parent is drawn among the earlier nodes that still have fewer than `max_width`
+    children (half of the time the most recent one, so that the trees have depth), which keeps
+    every parent before its children.  `chain=True` gives parent = previous node.  The draft
+    tokens are drawn again so that they fit the tree: node c's token comes from the draft
+    distribution AT its parent (draft_probs row of the parent node); siblings are independent
+    draws, and for a greedy (temperature 0) request the m-th child is the m-th most probable
+    token.  Nothing else of the step changes."""
+    seed = st.seed + 77 if seed is None else seed
+    g = np.random.Generator(np.random.PCG64(np.random.SeedSequence(seed)))
+    cu = st.cu_q
+    parents = np.full(st.total_q, -1, dtype=np.int32)
+    toks = None if st.draft_tokens is None else st.draft_tokens.copy()
+    for i in range(st.batch):
+        k = int(st.spec_lens[i])
+        par = np.full(k + 1, -1, dtype=np.int32)
+        n_child = np.zeros(k + 1, dtype=np.int64)
+        for c in range(1, k + 1):
+            if chain:
+                par[c] = c - 1
+            else:
+                free = np.nonzero(n_child[:c] < max_width)[0]
+                par[c] = free[-1] if g.random() < 0.5 else free[int(g.integers(0, free.shape[0]))]
+            rank = int(n_child[par[c]])
+            n_child[par[c]] += 1
+            if toks is None:
+                continue
+            qrow = to_f64(st.draft_probs[cu[i] - i + par[c]], st.probs_dtype)
+            if st.temperature[i] == 0.0:
+                t = int(np.argsort(-qrow, kind="stable")[rank])
+            else:
+                cdf = np.cumsum(qrow)
+                t = min(int(np.searchsorted(cdf, g.random() * cdf[-1], side="right")), st.vocab - 1)
+                while qrow[t] == 0.0 and t > 0:
+                    t -= 1
+            toks[cu[i] - i + c - 1] = t
+        parents[cu[i]:cu[i] + k + 1] = par
+    st.parents = parents
+    if toks is not None:
+        st.draft_tokens = toks
+    st.notes["tree_max_width"] = 1 if chain else max_width
+    return st
 
 
 def algorithmic_bytes(st: VerifyStep) -> Dict[str, int]:
