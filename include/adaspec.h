@@ -279,6 +279,80 @@ int adaspec_commit(const int32_t *out_tokens, const int32_t *out_accept_len,
                    const adaspec_commit_dims *dims, void *stream);
 
 /* ------------------------------------------------------------------------
+ * Tree verification: the drafts of a request form a token TREE instead of a
+ * chain.  The paper verifies chains and runs the tree-based system it compares
+ * with at tree width 1 (Sec. 7.1, baselines; Sec. 8 names tree-based
+ * speculative decoding as the other family), so these three calls lie beside
+ * its method: they are the token-tree verification of that baseline, restated.
+ * With parent = previous node they compute what the chain calls compute.
+ *
+ * Nodes.  Request i has n_i = k_i + 1 nodes = its query rows: node 0 is the
+ * last committed token (the root), nodes 1..k_i are drafts, ordered so that a
+ * parent comes before its children.  parents [TQ] int32 gives, for every row,
+ * the parent's index INSIDE the request (anything for the root; values outside
+ * [0, j) for node j are forced into that range).  At most 64 nodes per request:
+ * max_spec_len <= 63, else ADASPEC_ERR_UNSUPPORTED.
+ *
+ * adaspec_verify_attn_tree - as adaspec_verify_attn, except for what a row sees.
+ * Node j's K/V sit at cache position ctx_lens[i] - n_i + j (the nodes are
+ * appended in node order, e.g. by adaspec_kv_append); its row attends to the
+ * committed tokens 0 .. ctx_lens[i] - n_i - 1 and to the positions of node j's
+ * ancestors and its own.  Same dims, workspace size, plan modes (the ancestor
+ * masks belong to the reusable metadata: a PLAN_REUSE call must see the same
+ * parents) and error rules as adaspec_verify_attn.
+ * ---------------------------------------------------------------------- */
+int adaspec_verify_attn_tree(const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, const int32_t *ctx_lens,
+                             const int32_t *spec_lens, const int32_t *parents, void *out,
+                             const adaspec_attn_dims *dims,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * adaspec_accept_tree - acceptance walk over the tree of every request.
+ *   target_logits [TQ][V]  row of node j: the target's logits for the token after node j
+ *   draft_probs   [TD][V]  request i owns rows cu_q[i]-i ..; row j (0 <= j < k_i) is the draft
+ *                          distribution AT node j, which the tokens of j's children were drawn
+ *                          from (independent draws).  The last node of a request cannot have
+ *                          children and has no row; rows of other childless nodes are not read.
+ *   draft_tokens  [TD]     row j-1 of the request: token of node j
+ *   uniforms      [TQ][2]  the accept test of node c uses [cu_q[i]+c-1][0]; the draw at the node
+ *                          where the walk stops uses [cu_q[i]+u][1]
+ * Walk, from u = node 0, children of u in ascending node order:
+ *   T > 0 : P = softmax(logits_u / T).  Child c with token x is accepted iff
+ *           u0 < P[x] / q_u[x]  (q_u[x] == 0 accepts): emit x, go on from c.  After a
+ *           rejection r = max(0, P - q_u) and P = r / sum(r) (if sum(r) == 0, P stays).
+ *           No child accepted, or none exists: emit the smallest t whose inclusive prefix sum
+ *           of the last r (of P at a childless node) exceeds u1 * its total, and stop.
+ *   T == 0: z = argmax(logits_u) (lowest index on ties); the first child whose token is z is
+ *           accepted; if none, emit z and stop.
+ *   out_tokens     [B][out_stride]  tokens of the accepted nodes, the token emitted at the stop, then -1
+ *   out_accept_len [B]              accepted nodes a_i
+ *   out_path       [B][out_stride]  node indices of the accepted nodes in path order, then -1
+ * Dims and workspace as for adaspec_accept (dims->path must be AUTO or VECTOR: one portable kernel
+ * per node, any storage types and vocabulary size; every node of every tree is evaluated).  The
+ * cost of a node grows with the square of its number of rejected children.
+ */
+int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
+                        const int32_t *draft_tokens, const int32_t *parents, const float *uniforms,
+                        const int32_t *spec_lens, const float *temperature,
+                        int32_t *out_tokens, int32_t *out_accept_len, int32_t *out_path,
+                        const adaspec_accept_dims *dims,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * adaspec_kv_compact_path - AFTER tree acceptance, BEFORE adaspec_commit: move the K/V rows of
+ * the accepted nodes to where a chain would have put them.  Node out_path[i][j] (j < a_i) moves
+ * from position base + out_path[i][j] to base + 1 + j, base = ctx_lens[i] - n_i; the root stays.
+ * Afterwards adaspec_commit (with the same out_accept_len) keeps exactly those rows.
+ * ctx_lens / spec_lens are those of the verification step; path_stride = row stride of out_path.
+ * Uses of dims as in adaspec_kv_append.  Needs no workspace.
+ */
+int adaspec_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,
+                            const int32_t *ctx_lens, const int32_t *spec_lens,
+                            const int32_t *out_path, const int32_t *out_accept_len,
+                            const adaspec_attn_dims *dims, int32_t path_stride, void *stream);
+
+/* ------------------------------------------------------------------------
  * Draft-side sampling: the producer of draft_probs, draft_tokens and of the
  * confidence scores the speculative-length policy consumes (paper Sec. 4.2,
  * Eq. 6: a draft token's acceptance rate is modelled by the product of the

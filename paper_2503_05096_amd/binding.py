@@ -24,6 +24,7 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream":
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
     "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_resolved_path",
+    "adaspec_verify_attn_tree", "adaspec_accept_tree", "adaspec_kv_compact_path",
     "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
     "adaspec_draft_sample_workspace_bytes", "adaspec_draft_sample",
     "adaspec_set_timing_events",
@@ -92,6 +93,12 @@ def lib() -> C.CDLL:
         L.adaspec_accept.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
         L.adaspec_accept_resolved_path.restype = C.c_int
         L.adaspec_accept_resolved_path.argtypes = [vp, vp, C.POINTER(AcceptDims)]
+        L.adaspec_verify_attn_tree.restype = C.c_int
+        L.adaspec_verify_attn_tree.argtypes = [vp] * 8 + [C.POINTER(AttnDims), vp, C.c_size_t, vp]
+        L.adaspec_accept_tree.restype = C.c_int
+        L.adaspec_accept_tree.argtypes = [vp] * 10 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
+        L.adaspec_kv_compact_path.restype = C.c_int
+        L.adaspec_kv_compact_path.argtypes = [vp] * 7 + [C.POINTER(AttnDims), C.c_int32, vp]
         L.adaspec_check_ragged_inputs.restype = C.c_int
         L.adaspec_check_ragged_inputs.argtypes = [vp, vp, vp, C.POINTER(AttnDims), vp, vp]
         L.adaspec_kv_append.restype = C.c_int
@@ -178,11 +185,12 @@ def attn_dims(q, k_pages, block_table, *, max_spec_len: int, scale: float = 0.0,
 
 def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None, *,
                 max_spec_len: int, scale: float = 0.0, out_dtype: Optional[int] = None,
-                path: str = "auto", plan: str = "run", workspace=None, stream=None):
+                path: str = "auto", plan: str = "run", workspace=None, stream=None, parents=None):
     """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d].
 
     plan: "run" (build the ragged metadata, then run), "build" (metadata only; returns None) or
-    "reuse" (run with the metadata a previous call left in the same workspace)."""
+    "reuse" (run with the metadata a previous call left in the same workspace).
+    parents [TQ] int32 (a draft tree): adaspec_verify_attn_tree instead."""
     import torch
     dims = attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
                      out_dtype=out_dtype, path=path, plan=plan)
@@ -198,6 +206,16 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
         raise AdaspecError(L.adaspec_verify_attn(None, None, None, None, None, None, None, C.byref(dims),
                                                  None, 0, None) or -2, "adaspec_verify_attn (dims)")
     ws = _workspace(need, q.device, workspace)
+    if parents is not None:
+        assert parents.is_cuda and parents.is_contiguous() and parents.dtype == torch.int32
+        assert parents.shape == (q.shape[0],)
+        rc = L.adaspec_verify_attn_tree(q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
+                                        block_table.data_ptr(), ctx_lens.data_ptr(), spec_lens.data_ptr(),
+                                        parents.data_ptr(), None if out is None else out.data_ptr(),
+                                        C.byref(dims), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+        if rc != 0:
+            raise AdaspecError(rc, "adaspec_verify_attn_tree")
+        return out
     rc = L.adaspec_verify_attn(q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(),
                                block_table.data_ptr(), ctx_lens.data_ptr(), spec_lens.data_ptr(),
                                None if out is None else out.data_ptr(), C.byref(dims), ws.data_ptr(), ws.numel(),
@@ -261,6 +279,57 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
     if rc != 0:
         raise AdaspecError(rc, "adaspec_accept")
     return out_tokens, out_accept_len
+
+
+def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spec_lens, temperature, *,
+                max_spec_len: int, out_tokens=None, out_accept_len=None, out_path=None,
+                out_stride: Optional[int] = None, workspace=None, stream=None):
+    """adaspec_accept_tree; returns (out_tokens [B][out_stride], out_accept_len [B], out_path [B][out_stride])."""
+    import torch
+    for t in (uniforms, temperature, parents):
+        assert t.is_cuda and t.is_contiguous()
+    assert uniforms.dtype == torch.float32 and temperature.dtype == torch.float32 and parents.dtype == torch.int32
+    assert parents.shape == (target_logits.shape[0],)
+    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, "auto")
+    B, out_stride = dims.batch, dims.out_stride
+    dev = target_logits.device
+    if out_tokens is None:
+        out_tokens = torch.empty((B, out_stride), dtype=torch.int32, device=dev)
+    if out_accept_len is None:
+        out_accept_len = torch.empty((B,), dtype=torch.int32, device=dev)
+    if out_path is None:
+        out_path = torch.empty((B, out_stride), dtype=torch.int32, device=dev)
+    L = lib()
+    need = L.adaspec_accept_workspace_bytes(C.byref(dims))
+    ws = _workspace(max(need, 256), dev, workspace)
+    rc = L.adaspec_accept_tree(target_logits.data_ptr(), pp, tp, parents.data_ptr(), uniforms.data_ptr(),
+                               spec_lens.data_ptr(), temperature.data_ptr(), out_tokens.data_ptr(),
+                               out_accept_len.data_ptr(), out_path.data_ptr(), C.byref(dims), ws.data_ptr(),
+                               ws.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_accept_tree")
+    return out_tokens, out_accept_len, out_path
+
+
+def kv_compact_path(k_pages, v_pages, block_table, ctx_lens, spec_lens, out_path, out_accept_len, *,
+                    max_spec_len: int, stream=None) -> None:
+    """adaspec_kv_compact_path: moves the accepted nodes' K/V rows to chain positions, in place."""
+    import torch
+    num_pages, Hkv, P, d = k_pages.shape
+    B, max_pages = block_table.shape
+    for t in (k_pages, v_pages, block_table, ctx_lens, spec_lens, out_path, out_accept_len):
+        assert t.is_cuda and t.is_contiguous()
+    for t in (block_table, ctx_lens, spec_lens, out_path, out_accept_len):
+        assert t.dtype == torch.int32
+    assert v_pages.shape == k_pages.shape and v_pages.dtype == k_pages.dtype
+    dt = _dtype_code(k_pages)
+    dims = AttnDims(B, B, int(max_spec_len), Hkv, Hkv, d, P, num_pages, max_pages, dt, dt, PATH_AUTO, 0.0)
+    rc = lib().adaspec_kv_compact_path(k_pages.data_ptr(), v_pages.data_ptr(), block_table.data_ptr(),
+                                       ctx_lens.data_ptr(), spec_lens.data_ptr(), out_path.data_ptr(),
+                                       out_accept_len.data_ptr(), C.byref(dims), out_path.shape[1],
+                                       _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_kv_compact_path")
 
 
 def check_ragged_inputs(block_table, ctx_lens, spec_lens, dims: AttnDims, stream=None) -> int:

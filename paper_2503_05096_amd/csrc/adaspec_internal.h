@@ -28,6 +28,7 @@ struct AttnPlan {
     size_t off_unit_meta;   // int32[max_items][8] in schedule order: request, split, n_splits, L, n, cu_q, item, 0
     size_t off_row_rec;     // int32[TQ][4] per query row: request, n_splits, first split, row base (j * G)
     size_t off_sched;       // int32[rounds][W]: unit taken by workgroup w in each round, or -1 (matrix-core kernel)
+    size_t off_anc;         // uint64[TQ]: tree verification only, ancestor-or-self mask of each query row's node
     size_t off_part_ml;     // float[max_items][Hkv][max_rows][2]  (m in log2 units, l)
     size_t off_part_o;      // float[max_items][Hkv][max_rows][d]
     size_t total_bytes;
@@ -58,6 +59,7 @@ bool attn_fast_path_supported(const adaspec_attn_dims &d);
 struct AttnArgs {
     const void *q, *k_pages, *v_pages;
     const int32_t *block_table, *ctx_lens, *spec_lens;
+    const int32_t *parents = nullptr;   // tree verification: parent node of every query row, else NULL
     void *out;
     adaspec_attn_dims dims;
     float scale_log2;       // scale * log2(e)
@@ -78,6 +80,8 @@ constexpr int kMaxSchedW = 1024;
 void attn_mfma_shape(AttnArgs &a);
 
 hipError_t launch_attn_plan(const AttnArgs &a);
+// tree verification: ancestor masks of all query rows (after the plan kernel: it reads cu_q)
+hipError_t launch_tree_masks(const AttnArgs &a);
 hipError_t launch_attn_vector(const AttnArgs &a);
 hipError_t launch_attn_mfma(const AttnArgs &a);
 hipError_t launch_attn_combine(const AttnArgs &a);
@@ -132,6 +136,13 @@ hipError_t launch_accept_resolve(const AcceptArgs &a);
 bool accept_split_supported(const adaspec_accept_dims &d);
 size_t accept_split_part_bytes(int batch);
 hipError_t launch_accept_split(const AcceptArgs &a);
+
+// tree verification (tree.hip): every node's acceptance, then the walk; needs the accept plan's cu_q / row_req
+hipError_t launch_accept_tree(const AcceptArgs &a, const int32_t *parents, int32_t *out_path);
+hipError_t launch_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,
+                                  const int32_t *ctx_lens, const int32_t *spec_lens,
+                                  const int32_t *out_path, const int32_t *out_accept_len,
+                                  const adaspec_attn_dims &d, int path_stride, hipStream_t stream);
 
 hipError_t launch_check_ragged(const int32_t *block_table, const int32_t *ctx_lens,
                                const int32_t *spec_lens, const adaspec_attn_dims &d,

@@ -88,6 +88,7 @@ AttnPlan make_attn_plan(const adaspec_attn_dims &d, bool fast_path)
         const size_t units = (size_t)p.max_items * d.n_kv_heads * attn_row_groups(p.max_rows);
         p.off_sched = off;  off = align_up(off + (fast_path ? units + kMaxSchedW : 1) * 4, 256);
     }
+    p.off_anc = off;        off = align_up(off + (size_t)(d.total_q > 0 ? d.total_q : 1) * 8, 256);
     p.off_part_ml = off;
     off = align_up(off + (size_t)p.max_items * d.n_kv_heads * p.max_rows * 2 * sizeof(float), 256);
     p.off_part_o = off;
@@ -141,14 +142,18 @@ size_t adaspec_verify_attn_workspace_bytes(const adaspec_attn_dims *dims)
     return make_attn_plan(*dims, attn_use_fast(*dims)).total_bytes;
 }
 
-int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
-                        const int32_t *block_table, const int32_t *ctx_lens,
-                        const int32_t *spec_lens, void *out, const adaspec_attn_dims *dims,
-                        void *workspace, size_t workspace_bytes, void *stream)
+// chain (parents == NULL, tree == false) and tree verification share everything but the mask
+static int verify_attn_impl(const void *q, const void *k_pages, const void *v_pages,
+                            const int32_t *block_table, const int32_t *ctx_lens,
+                            const int32_t *spec_lens, const int32_t *parents, bool tree, void *out,
+                            const adaspec_attn_dims *dims,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = validate_attn_dims(dims);
     if (rc != ADASPEC_OK) return rc;
+    if (tree && dims->max_spec_len > 63) return ADASPEC_ERR_UNSUPPORTED;
     if (dims->batch == 0) return ADASPEC_OK;
+    if (tree && !parents) return ADASPEC_ERR_NULL;
     const bool plan_only = dims->plan_mode == ADASPEC_PLAN_BUILD_ONLY;
     if (!block_table || !ctx_lens || !spec_lens || !workspace) return ADASPEC_ERR_NULL;
     if (!plan_only && (!q || !k_pages || !v_pages || !out)) return ADASPEC_ERR_NULL;
@@ -161,13 +166,17 @@ int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
     if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;
     a.q = q; a.k_pages = k_pages; a.v_pages = v_pages;
     a.block_table = block_table; a.ctx_lens = ctx_lens; a.spec_lens = spec_lens;
+    a.parents = tree ? parents : nullptr;
     a.out = out; a.dims = *dims; a.ws = static_cast<char *>(workspace);
     a.stream = static_cast<hipStream_t>(stream);
     const float scale = dims->scale > 0.0f ? dims->scale : 1.0f / sqrtf((float)dims->head_dim);
     a.scale_log2 = scale * 1.4426950408889634f;
 
     if (fast) attn_mfma_shape(a);
-    if (dims->plan_mode != ADASPEC_PLAN_REUSE && launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (dims->plan_mode != ADASPEC_PLAN_REUSE) {
+        if (launch_attn_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        if (tree && launch_tree_masks(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    }
     if (plan_only) return ADASPEC_OK;
     if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_start[0], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
@@ -177,6 +186,25 @@ int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
         return ADASPEC_ERR_HIP;
     if (launch_attn_combine(a) != hipSuccess) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
+}
+
+int adaspec_verify_attn(const void *q, const void *k_pages, const void *v_pages,
+                        const int32_t *block_table, const int32_t *ctx_lens,
+                        const int32_t *spec_lens, void *out, const adaspec_attn_dims *dims,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    return verify_attn_impl(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, nullptr, false, out, dims,
+                            workspace, workspace_bytes, stream);
+}
+
+int adaspec_verify_attn_tree(const void *q, const void *k_pages, const void *v_pages,
+                             const int32_t *block_table, const int32_t *ctx_lens,
+                             const int32_t *spec_lens, const int32_t *parents, void *out,
+                             const adaspec_attn_dims *dims,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    return verify_attn_impl(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, parents, true, out, dims,
+                            workspace, workspace_bytes, stream);
 }
 
 size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims)
@@ -266,6 +294,62 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     if (launch_accept_emit(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
+                        const int32_t *draft_tokens, const int32_t *parents, const float *uniforms,
+                        const int32_t *spec_lens, const float *temperature,
+                        int32_t *out_tokens, int32_t *out_accept_len, int32_t *out_path,
+                        const adaspec_accept_dims *dims,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_accept_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    if (dims->path != ADASPEC_PATH_AUTO && dims->path != ADASPEC_PATH_VECTOR) return ADASPEC_ERR_UNSUPPORTED;
+    if (dims->max_spec_len > 63) return ADASPEC_ERR_UNSUPPORTED;
+    if (dims->batch == 0) return ADASPEC_OK;
+    if (!target_logits || !parents || !uniforms || !spec_lens || !temperature || !out_tokens ||
+        !out_accept_len || !out_path || !workspace)
+        return ADASPEC_ERR_NULL;
+    if (dims->total_draft > 0 && (!draft_probs || !draft_tokens)) return ADASPEC_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
+    AcceptArgs a;
+    a.plan = make_accept_plan(*dims);
+    if (workspace_bytes < a.plan.total_bytes) return ADASPEC_ERR_WORKSPACE;
+    a.logits = target_logits; a.probs = draft_probs; a.draft_tokens = draft_tokens;
+    a.uniforms = uniforms; a.spec_lens = spec_lens; a.temperature = temperature;
+    a.out_tokens = out_tokens; a.out_accept_len = out_accept_len;
+    a.dims = *dims; a.ws = static_cast<char *>(workspace);
+    a.stream = static_cast<hipStream_t>(stream);
+    if (launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (launch_accept_tree(a, parents, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
+int adaspec_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,
+                            const int32_t *ctx_lens, const int32_t *spec_lens,
+                            const int32_t *out_path, const int32_t *out_accept_len,
+                            const adaspec_attn_dims *d, int32_t path_stride, void *stream)
+{
+    if (!d) return ADASPEC_ERR_NULL;
+    if (d->batch < 0 || d->max_spec_len < 0 || path_stride < d->max_spec_len + 1) return ADASPEC_ERR_DIM;
+    if (d->n_kv_heads <= 0 || d->head_dim <= 0 || d->page_size <= 0) return ADASPEC_ERR_DIM;
+    if (d->num_pages <= 0 || d->max_pages_per_req <= 0) return ADASPEC_ERR_DIM;
+    if (!dtype_ok(d->dtype)) return ADASPEC_ERR_DTYPE;
+    if ((d->head_dim * (d->dtype == ADASPEC_F32 ? 4 : 2)) % 16) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->batch > 65535) return ADASPEC_ERR_UNSUPPORTED;
+    if (d->batch == 0) return ADASPEC_OK;
+    if (!k_pages || !v_pages || !block_table || !ctx_lens || !spec_lens || !out_path || !out_accept_len)
+        return ADASPEC_ERR_NULL;
+    if (!aligned16(k_pages) || !aligned16(v_pages)) return ADASPEC_ERR_ALIGN;
+    if (launch_kv_compact_path(k_pages, v_pages, block_table, ctx_lens, spec_lens, out_path, out_accept_len, *d,
+                               path_stride, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
 

@@ -18,6 +18,11 @@
 // channels per page), transposed 4x8 in registers with byte permutes and written
 // to a wavefront-private 8 KB LDS tile laid out so that both the 16-byte writes
 // and the 16-byte operand reads are bank-conflict free.
+//
+// kTree: the drafts of a request form a tree instead of a chain.  A row then sees the committed
+// tokens and, of the request's new positions, those of its own ancestors: a 64-bit mask per query
+// row (bit a = node a is the row's node or an ancestor of it), prepared once per verification pass.
+// Only the blocks that hold new positions look at it; the instantiations for chains are untouched.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 
@@ -92,12 +97,12 @@ struct Unit {
     int64_t qrow0, bt_off;      // first query row; offset of the request's row in block_table
 };
 
-template <class T, int RT>
+template <class T, int RT, bool kTree>
 __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     const char *__restrict__ q, const char *__restrict__ k_pages, const char *__restrict__ v_pages,
     const int32_t *__restrict__ block_table, void *__restrict__ out, int32_t *__restrict__ header,
     const int32_t *__restrict__ unit_meta, const int32_t *__restrict__ sched,
-    float *__restrict__ part_ml, float *__restrict__ part_o,
+    const unsigned long long *__restrict__ anc, float *__restrict__ part_ml, float *__restrict__ part_o,
     int Hq, int Hkv, int max_pages_per_req, int max_rows, int n_row_groups, float scale_log2,
     int out_dtype)
 {
@@ -107,6 +112,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
     __shared__ __attribute__((aligned(16))) char smem[kSmem];
     __shared__ __attribute__((aligned(16))) uint4 q_lds[RT * 4 * 64];   // Q^T operands, MFMA lane order
     __shared__ float s_m[kWaves][kRows], s_l[kWaves][kRows], s_mstar[kRows];
+    __shared__ unsigned long long s_anc[kTree ? kRows : 1];         // ancestor mask of each row of the unit
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave-uniform by construction
@@ -204,10 +210,21 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
         }
     };
 
+    // tree: the ancestor mask of row tid of the unit (threads 0 .. kRows-1), requested with the Q rows
+    auto load_anc = [&](const Unit &u) -> unsigned long long {
+        const int row = u.r0 + tid;
+        return (tid < kRows && row < u.rows) ? anc[u.qrow0 + row / G] : 0ull;
+    };
+
     Unit cur, nxt;
     bool have = next_unit(cur);
     uint4 qv[RT];
-    if (have) { load_q(cur, qv); first_loads(cur); }
+    unsigned long long av = 0ull;
+    if (have) {
+        load_q(cur, qv);
+        if constexpr (kTree) av = load_anc(cur);
+        first_loads(cur);
+    }
 
     while (have) {
         const Unit u = cur;
@@ -215,6 +232,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
         const int first_masked = u.L - u.n + 1;                    // tokens >= this are hidden from some row
 #pragma unroll
         for (int k = 0; k < RT; ++k) q_lds[tid + 256 * k] = qv[k];
+        if constexpr (kTree) { if (tid < kRows) s_anc[tid] = av; }
         int pos[RT];
 #pragma unroll
         for (int nt = 0; nt < RT; ++nt) {
@@ -268,11 +286,25 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
 #pragma unroll
                     for (int r = 0; r < 4; ++r) sv[4 * mt + r] = sacc[nt][mt][r];
                 if (need_mask) {
-                    const int lim = min(pos[nt], u.t1 - 1);
+                    if constexpr (kTree) {
+                        // committed tokens are visible to every real row; new position base + a only
+                        // if bit a of the row's mask is set (padding rows: pos < 0, mask 0)
+                        const unsigned long long am = s_anc[16 * nt + n16];
+                        const int base = u.L - u.n;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int t = tb + 16 * (e >> 2) + 4 * g + (e & 3);
-                        sv[e] = (t <= lim) ? sv[e] : -INFINITY;
+                        for (int e = 0; e < 8; ++e) {
+                            const int t = tb + 16 * (e >> 2) + 4 * g + (e & 3);
+                            const int rel = t - base;
+                            const bool vis = t < u.t1 && (rel < 0 ? pos[nt] >= 0 : ((am >> (rel & 63)) & 1ull) != 0);
+                            sv[e] = vis ? sv[e] : -INFINITY;
+                        }
+                    } else {
+                        const int lim = min(pos[nt], u.t1 - 1);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int t = tb + 16 * (e >> 2) + 4 * g + (e & 3);
+                            sv[e] = (t <= lim) ? sv[e] : -INFINITY;
+                        }
                     }
                 }
                 float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
@@ -362,7 +394,11 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
             lsum[nt] += __shfl_xor(lsum[nt], 32, kWave);
             if (g == 0) s_m[wv][16 * nt + n16] = m[nt];
         }
-        if (have_next) { load_q(nxt, qv); first_loads(nxt); }
+        if (have_next) {
+            load_q(nxt, qv);
+            if constexpr (kTree) av = load_anc(nxt);
+            first_loads(nxt);
+        }
         __syncthreads();            // s_m complete; every wavefront is done with its V^T tile and q_lds
 
         // ---- merge the four wavefronts' states through LDS --------------------------------
@@ -452,13 +488,13 @@ static int device_cus()
     return cus;
 }
 
-template <typename T, int RT>
+template <typename T, int RT, bool kTree>
 static int attn_mfma_slots()
 {
     static int slots = 0;
     if (slots == 0) {
         int per_cu = 1;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT>, 256, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<T, RT, kTree>, 256, 0) != hipSuccess)
             per_cu = 1;
         const int n = device_cus() * (per_cu > 0 ? per_cu : 1);
         slots = n < kMaxSchedW ? n : kMaxSchedW;
@@ -467,17 +503,21 @@ static int attn_mfma_slots()
 }
 
 template <typename F>
-static void with_instance(int dtype, int rt, F &&f)
+static void with_instance(int dtype, int rt, bool tree, F &&f)
 {
-    auto with_rt = [&](auto tag) {
+    auto with_rt = [&](auto tag, auto tree_tag) {
         switch (rt) {
-        case 1: f(tag, std::integral_constant<int, 1>{}); break;
-        case 2: f(tag, std::integral_constant<int, 2>{}); break;
-        default: f(tag, std::integral_constant<int, 3>{}); break;
+        case 1: f(tag, std::integral_constant<int, 1>{}, tree_tag); break;
+        case 2: f(tag, std::integral_constant<int, 2>{}, tree_tag); break;
+        default: f(tag, std::integral_constant<int, 3>{}, tree_tag); break;
         }
     };
-    if (dtype == ADASPEC_F16) with_rt(F16{});
-    else with_rt(BF16{});
+    auto with_tree = [&](auto tag) {
+        if (tree) with_rt(tag, std::true_type{});
+        else with_rt(tag, std::false_type{});
+    };
+    if (dtype == ADASPEC_F16) with_tree(F16{});
+    else with_tree(BF16{});
 }
 
 void attn_mfma_shape(AttnArgs &a)
@@ -488,8 +528,8 @@ void attn_mfma_shape(AttnArgs &a)
     a.rows_per_group = 16 * rt;
     const int64_t max_units = (int64_t)p.max_items * a.dims.n_kv_heads * a.n_row_groups;
     int slots = 1;
-    with_instance(a.dims.dtype, rt, [&](auto tag, auto rt_tag) {
-        slots = attn_mfma_slots<decltype(tag), decltype(rt_tag)::value>();
+    with_instance(a.dims.dtype, rt, a.parents != nullptr, [&](auto tag, auto rt_tag, auto tree_tag) {
+        slots = attn_mfma_slots<decltype(tag), decltype(rt_tag)::value, decltype(tree_tag)::value>();
     });
     a.sched_w = (int)(max_units < slots ? max_units : slots);
     a.sched_cus = device_cus();
@@ -500,14 +540,15 @@ hipError_t launch_attn_mfma(const AttnArgs &a)
     const AttnPlan &p = a.plan;
     const adaspec_attn_dims &d = a.dims;
     if (a.sched_w <= 0) return hipSuccess;                          // no work item can exist
-    with_instance(d.dtype, attn_row_tiles(p.max_rows), [&](auto tag, auto rt_tag) {
+    with_instance(d.dtype, attn_row_tiles(p.max_rows), a.parents != nullptr, [&](auto tag, auto rt_tag, auto tree_tag) {
         using T = decltype(tag);
         constexpr int RT = decltype(rt_tag)::value;
-        hipLaunchKernelGGL((attn_mfma_kernel<T, RT>), dim3(a.sched_w), dim3(256), 0, a.stream,
+        constexpr bool kTree = decltype(tree_tag)::value;
+        hipLaunchKernelGGL((attn_mfma_kernel<T, RT, kTree>), dim3(a.sched_w), dim3(256), 0, a.stream,
                            (const char *)a.q, (const char *)a.k_pages, (const char *)a.v_pages,
                            a.block_table, a.out, (int32_t *)(a.ws + p.off_header),
                            (const int32_t *)(a.ws + p.off_unit_meta), (const int32_t *)(a.ws + p.off_sched),
-                           (float *)(a.ws + p.off_part_ml), (float *)(a.ws + p.off_part_o), d.n_q_heads,
+                           (const unsigned long long *)(a.ws + p.off_anc), (float *)(a.ws + p.off_part_ml), (float *)(a.ws + p.off_part_o), d.n_q_heads,
                            d.n_kv_heads, d.max_pages_per_req, p.max_rows, a.n_row_groups, a.scale_log2,
                            d.out_dtype);
     });

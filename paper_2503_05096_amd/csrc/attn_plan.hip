@@ -23,7 +23,8 @@ __host__ __device__ inline int log2_exact(int v)          // v is a power of two
 // clamped to the host-declared bounds so that inconsistent device data cannot make the library
 // write outside its workspace.
 //
-// W > 0 (matrix-core kernel): writes row_rec, unit_meta, the schedule table and the header.
+// W > 0 (matrix-core kernel): writes row_rec, unit_meta, the schedule table and the header
+// (cu_q and split_base only when asked for, or when the requests do not fit on chip).
 // W = 0 (vector kernel): writes cu_q, split_base, item_req, item_order, row_rec and the header.
 //
 // The kernel is a chain of short dependent phases, so what it costs is latency: the barriers
@@ -36,7 +37,8 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
     int max_spec_len, int split_log2, int block_log2, int max_items, int G, int32_t *__restrict__ header,
     int32_t *__restrict__ cu_q, int32_t *__restrict__ split_base, int32_t *__restrict__ item_req,
     int32_t *__restrict__ item_order, int32_t *__restrict__ unit_meta, int32_t *__restrict__ row_rec,
-    int W, int Hkv, int n_row_groups, int rows_per_group, int32_t *__restrict__ sched, int cus)
+    int W, int Hkv, int n_row_groups, int rows_per_group, int32_t *__restrict__ sched, int cus,
+    int want_cu_q)
 {
     __shared__ int tot_n[kPlanThreads / kWave], tot_s[kPlanThreads / kWave];
     __shared__ int carry[2];
@@ -71,7 +73,8 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
         }
         const int my_q = pre_n + inc_n - n, my_s = pre_s + inc_s - ns;
         if (i < B) {
-            if (!fast || !reqs_on_chip) { cu_q[i] = my_q; split_base[i] = my_s; }
+            // (want_cu_q: a later kernel of the call reads cu_q from the workspace, e.g. the tree masks)
+            if (!fast || !reqs_on_chip || want_cu_q) { cu_q[i] = my_q; split_base[i] = my_s; }
             if (base == 0) req[tid] = make_int4(L, n, my_q, my_s);
             // record for the combine kernel: (request, number of splits, first split, first row index of
             // this query row inside its (item, kv head) partial block)
@@ -231,7 +234,7 @@ hipError_t launch_attn_plan(const AttnArgs &a)
                        (int32_t *)(a.ws + p.off_item_req), (int32_t *)(a.ws + p.off_item_order),
                        (int32_t *)(a.ws + p.off_unit_meta), (int32_t *)(a.ws + p.off_row_rec), a.sched_w,
                        a.dims.n_kv_heads, a.n_row_groups, a.rows_per_group, (int32_t *)(a.ws + p.off_sched),
-                       a.sched_cus);
+                       a.sched_cus, a.parents != nullptr ? 1 : 0);
     return hipGetLastError();
 }
 

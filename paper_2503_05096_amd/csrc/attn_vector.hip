@@ -23,7 +23,7 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
     const int32_t *__restrict__ spec_lens, void *__restrict__ out, int32_t *__restrict__ header,
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ split_base,
     const int32_t *__restrict__ item_req, const int32_t *__restrict__ item_order,
-    float *__restrict__ part_ml, float *__restrict__ part_o,
+    const unsigned long long *__restrict__ anc, float *__restrict__ part_ml, float *__restrict__ part_o,
     int Hq, int Hkv, int d, int P, int max_pages_per_req, int max_rows, int n_row_chunks,
     int split_tokens, int block_tokens, float scale_log2, int out_dtype)
 {
@@ -61,6 +61,13 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
         }
         __syncthreads();
 
+        // tree verification (anc != NULL): bit a of a row's mask = the request's node a is the row's
+        // node or one of its ancestors; of the new positions L - n + a a row sees exactly those
+        unsigned long long am[kRC];
+#pragma unroll
+        for (int r = 0; r < kRC; ++r)
+            am[r] = (anc && r0 + r < rows) ? anc[qbase + (r0 + r) / G] : 0ull;
+
         float m[kRC], l[kRC], acc[kRC][4];
 #pragma unroll
         for (int r = 0; r < kRC; ++r) {
@@ -93,7 +100,8 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
             for (int r = 0; r < kRC; ++r) {
                 const int row = r0 + r;
                 const int pos = L - n + row / G;            // last token this row may see
-                const bool vis = valid && row < rows && t <= pos;
+                bool vis = valid && row < rows && t <= pos;
+                if (anc && t >= L - n) vis = vis && ((am[r] >> ((t - (L - n)) & 63)) & 1ull) != 0;
                 const float sv = vis ? sc[r] * scale_log2 : -INFINITY;
                 const float bm = wave_max(sv);
                 const float mn = fmaxf(m[r], bm);
@@ -170,7 +178,9 @@ hipError_t launch_attn_vector(const AttnArgs &a)
                            (int32_t *)(a.ws + p.off_header), (const int32_t *)(a.ws + p.off_cu_q),
                            (const int32_t *)(a.ws + p.off_split_base),
                            (const int32_t *)(a.ws + p.off_item_req),
-                           (const int32_t *)(a.ws + p.off_item_order), (float *)(a.ws + p.off_part_ml),
+                           (const int32_t *)(a.ws + p.off_item_order),
+                           a.parents ? (const unsigned long long *)(a.ws + p.off_anc) : nullptr,
+                           (float *)(a.ws + p.off_part_ml),
                            (float *)(a.ws + p.off_part_o), d.n_q_heads, d.n_kv_heads, d.head_dim,
                            d.page_size, d.max_pages_per_req, p.max_rows, n_row_chunks, p.split_tokens,
                            p.block_tokens, a.scale_log2, d.out_dtype);

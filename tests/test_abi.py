@@ -233,3 +233,39 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         binding.lib()
+
+
+# ------------------------------------------------------------------ tree verification
+def test_tree_calls_validate_on_the_host():
+    L = pkg.lib()
+    d = _attn_dims()
+    tree_attn = lambda dims, ptrs, ws=PTR, nbytes=1 << 40: L.adaspec_verify_attn_tree(*ptrs, C.byref(dims), ws, nbytes, None)
+    assert tree_attn(d, [PTR] * 6 + [None, PTR]) == -1                      # parents missing
+    assert tree_attn(_attn_dims(batch=-1), [PTR] * 8) == -2
+    assert tree_attn(_attn_dims(total_q=66, max_spec_len=64), [PTR] * 8) == -6   # more than 64 nodes per request
+    assert tree_attn(d, [PTR] * 8, nbytes=16) == -5
+    assert tree_attn(d, [PTR + 8] + [PTR] * 7) == -4
+    assert tree_attn(_attn_dims(batch=0, total_q=0), [None] * 8, None, 0) == 0
+
+    a = _accept_dims()
+    tree_acc = lambda dims, ptrs, ws=PTR, nbytes=1 << 40: L.adaspec_accept_tree(*ptrs, C.byref(dims), ws, nbytes, None)
+    for k in (0, 3, 4, 5, 6, 7, 8, 9):
+        p = [PTR] * 10
+        p[k] = None
+        assert tree_acc(a, p) == -1, k
+    assert tree_acc(_accept_dims(path=2), [PTR] * 10) == -6                 # only the portable kernel
+    assert tree_acc(_accept_dims(total_q=68, total_draft=66, max_spec_len=64, out_stride=65), [PTR] * 10) == -6
+    assert tree_acc(_accept_dims(out_stride=3), [PTR] * 10) == -2
+    assert tree_acc(a, [PTR] * 10, nbytes=16) == -5
+    assert tree_acc(a, [PTR] * 10, ws=PTR + 64) == -4
+    assert tree_acc(_accept_dims(batch=0, total_q=0, total_draft=0), [None] * 10, None, 0) == 0
+
+    compact = lambda dims, ptrs, stride=4: L.adaspec_kv_compact_path(*ptrs, C.byref(dims), stride, None)
+    for k in range(7):
+        p = [PTR] * 7
+        p[k] = None
+        assert compact(d, p) == -1, k
+    assert compact(d, [PTR] * 7, stride=3) == -2                            # narrower than max_spec_len + 1
+    assert compact(d, [PTR + 8] + [PTR] * 6) == -4
+    assert compact(_attn_dims(head_dim=4), [PTR] * 7) == -6                 # rows are moved in 16-byte pieces
+    assert compact(_attn_dims(batch=0, total_q=0), [None] * 7) == 0
