@@ -58,12 +58,20 @@ def cpu_baseline(st) -> dict:
     reps, t_attn, t_acc = 0, 0.0, 0.0
     while reps < 3 or (t_attn + t_acc < 2.0 and reps < 50):       # a few seconds of wall time on all cores
         t0 = time.perf_counter()
-        oracle.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
-                           dtype=st.dtype, want_rounded=False)
-        t1 = time.perf_counter()
-        oracle.accept(st.target_logits, st.draft_probs, st.draft_tokens, st.uniforms, st.spec_lens,
-                      st.temperature, logits_dtype=st.logits_dtype, probs_dtype=st.probs_dtype,
-                      want_row_info=False)
+        if st.parents is not None:
+            oracle.verify_attn_tree(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                                    st.parents, dtype=st.dtype, want_rounded=False)
+            t1 = time.perf_counter()
+            oracle.accept_tree(st.target_logits, st.draft_probs, st.draft_tokens, st.parents, st.uniforms,
+                               st.spec_lens, st.temperature, logits_dtype=st.logits_dtype,
+                               probs_dtype=st.probs_dtype)
+        else:
+            oracle.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                               dtype=st.dtype, want_rounded=False)
+            t1 = time.perf_counter()
+            oracle.accept(st.target_logits, st.draft_probs, st.draft_tokens, st.uniforms, st.spec_lens,
+                          st.temperature, logits_dtype=st.logits_dtype, probs_dtype=st.probs_dtype,
+                          want_row_info=False)
         t2 = time.perf_counter()
         t_attn += t1 - t0
         t_acc += t2 - t1
@@ -83,7 +91,7 @@ def cpu_baseline(st) -> dict:
     return {"value": st.total_q * reps / (t_attn + t_acc), "unit": "verified query-tokens/s",
             "cores": cores, "kind": "oracle", "config1_single_thread_s": t_cfg1,
             "sample": f"{reps} full steps of {st.name} (all {st.batch} requests, one attention layer + acceptance; "
-                      f"the sequential oracle stops at each request's first rejection); per step: "
+                      f"the sequential oracle stops where each request's walk stops); per step: "
                       f"attention {t_attn / reps:.3f} s, acceptance {t_acc / reps:.3f} s"}
 
 
@@ -101,6 +109,9 @@ def main() -> int:
                          "inputs in the 256 MB memory-side cache (1 = warm-cache run, labelled as such)")
     ap.add_argument("--hot-path-only", action="store_true",
                     help="skip the extra measurements (whole 32-layer pass, steps around the hot path)")
+    ap.add_argument("--tree", type=int, default=0, metavar="WIDTH",
+                    help="verify draft TREES instead of chains: the drafts of every request are rewired into a tree "
+                         "with up to WIDTH children per node (tree attention + tree acceptance; hot path only)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="run only a plain 512 MiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -127,7 +138,16 @@ def main() -> int:
     cfg = int(args.workload[3])
     attn_path = "auto" if args.path in ("stream", "two_pass") else args.path
     st = W.make_verify_step(cfg, greedy=args.workload.endswith("g"), poison=False)
-    nbytes = W.algorithmic_bytes(st)
+    tree = args.tree > 0
+    if tree:
+        if args.path not in ("auto", "vector"):
+            print("bench.py: --tree runs the tree calls (attention: auto or vector; acceptance: the per-node kernel)",
+                  file=sys.stderr)
+            return 2
+        W.attach_tree(st, max_width=args.tree)
+        st.name += f"-tree{args.tree}"
+        args.hot_path_only = True
+    nbytes = W.algorithmic_bytes_tree(st) if tree else W.algorithmic_bytes(st)
     torch.cuda.set_device(0)
     dev0 = to_device(st, "cuda:0")
     ncopies = max(1, args.copies)
@@ -157,13 +177,27 @@ def main() -> int:
     ws_acc = torch.empty(max(pkg.lib().adaspec_accept_workspace_bytes(C.byref(acc_dims)), 256),
                          dtype=torch.uint8, device="cuda:0")
 
+    tpath_out = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
+
+    def run_attn(dv, **kw):
+        pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens,
+                        out, max_spec_len=kmax, path=attn_path, workspace=ws_attn,
+                        parents=dv.parents if tree else None, **kw)
+
+    def run_accept(dv, **kw):
+        if tree:
+            pkg.accept_tree(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.parents, dv.uniforms,
+                            dv.spec_lens, dv.temperature, max_spec_len=kmax, out_tokens=toks,
+                            out_accept_len=alen, out_path=tpath_out, workspace=ws_acc, **kw)
+        else:
+            pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
+                       dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
+                       path=args.path, workspace=ws_acc, **kw)
+
     def step(k=0):
         dv = devs[k % ncopies]
-        pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens,
-                        out, max_spec_len=kmax, path=attn_path, workspace=ws_attn, stream=stream)
-        pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
-                   dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
-                   path=args.path, workspace=ws_acc, stream=stream)
+        run_attn(dv, stream=stream)
+        run_accept(dv, stream=stream)
 
     # a plain device-to-device copy on the same box, for scale (reads + writes 2 x 512 MiB per copy)
     cp_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda:0")
@@ -204,8 +238,8 @@ def main() -> int:
     # Which acceptance kernels ran decides what counts as algorithmic bytes: the per-row paths read every
     # logits row and every sampled draft-probability row; the two-pass path applies the sequential rule
     # while it works and never reads the rows it skips, so those bytes are not counted for it.
-    accept_path = pkg.accept_resolved_path(dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.spec_lens,
-                                           max_spec_len=kmax, path=args.path)
+    accept_path = "tree (per-node kernel)" if tree else pkg.accept_resolved_path(
+        dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.spec_lens, max_spec_len=kmax, path=args.path)
     per_row_accept_bytes = nbytes["accept"]
     if accept_path == "two_pass":
         skip = W.accept_bytes_skipping_form(st, alen.cpu().numpy())
@@ -217,11 +251,8 @@ def main() -> int:
         gph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gph, stream=stream):
             dv = devs[c]
-            pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens, out,
-                            max_spec_len=kmax, path=attn_path, workspace=ws_attn)
-            pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
-                       dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
-                       path=args.path, workspace=ws_acc)
+            run_attn(dv)
+            run_accept(dv)
         graphs.append(gph)
     with torch.cuda.stream(stream):
         for k in range(6):
@@ -288,7 +319,10 @@ def main() -> int:
                      "kernel_ms": spread(attn_all)},
         "roofline_accept": {"bound": "hbm",
                             "kernel": "acceptance kernels between the library's events (two-pass form: both passes)",
-                            "note": ("two-pass form: algorithmic bytes = every draft row's logits row once (accept "
+                            "note": ("tree, per-node form: the logits row of every node once, and the draft-probability row "
+                                     "of every sampled node that has children once"
+                                     if tree else
+                                     "two-pass form: algorithmic bytes = every draft row's logits row once (accept "
                                      "test) + per request the deciding row (with its draft-probability row if it is a "
                                      "rejected sampled draft); rows the form skips are NOT counted"
                                      if accept_path == "two_pass" else
@@ -310,6 +344,11 @@ def main() -> int:
         if not args.no_cpu_baseline:
             rec["cpu_baseline"] = cpu_baseline(st)
             rec["cpu_baseline"]["gpu_over_oracle"] = rec["value"] / rec["cpu_baseline"]["value"]
+        if tree:
+            a_np = alen.cpu().numpy()
+            rec["config"]["tree"] = {"max_children_per_node": args.tree,
+                                     "mean_accepted_nodes": float(a_np.mean()),
+                                     "nodes_with_children": int(W.tree_internal_nodes(st).sum())}
         print(json.dumps(rec))
         return 0
 

@@ -283,14 +283,15 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
 
 def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spec_lens, temperature, *,
                 max_spec_len: int, out_tokens=None, out_accept_len=None, out_path=None,
-                out_stride: Optional[int] = None, workspace=None, stream=None):
-    """adaspec_accept_tree; returns (out_tokens [B][out_stride], out_accept_len [B], out_path [B][out_stride])."""
+                out_stride: Optional[int] = None, path: str = "auto", workspace=None, stream=None):
+    """adaspec_accept_tree; returns (out_tokens [B][out_stride], out_accept_len [B], out_path [B][out_stride]).
+    path: "auto", "vector" (portable per-node kernel) or "fast" (1024-thread per-node kernel)."""
     import torch
     for t in (uniforms, temperature, parents):
         assert t.is_cuda and t.is_contiguous()
     assert uniforms.dtype == torch.float32 and temperature.dtype == torch.float32 and parents.dtype == torch.int32
     assert parents.shape == (target_logits.shape[0],)
-    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, "auto")
+    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
     B, out_stride = dims.batch, dims.out_stride
     dev = target_logits.device
     if out_tokens is None:

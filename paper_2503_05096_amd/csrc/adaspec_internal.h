@@ -137,8 +137,12 @@ bool accept_split_supported(const adaspec_accept_dims &d);
 size_t accept_split_part_bytes(int batch);
 hipError_t launch_accept_split(const AcceptArgs &a);
 
-// tree verification (tree.hip): every node's acceptance, then the walk; needs the accept plan's cu_q / row_req
-hipError_t launch_accept_tree(const AcceptArgs &a, const int32_t *parents, int32_t *out_path);
+// tree verification (tree.hip, tree_fast.hip): every node's acceptance, then the walk; needs the accept plan's cu_q / row_req
+// per-node kernels write (next node or -1, token if the walk stops here) into row_flag / row_cand:
+// the portable one (any types and sizes) and the 1024-thread one (shapes of the register-resident chain kernel)
+hipError_t launch_accept_tree_nodes(const AcceptArgs &a, const int32_t *parents);
+hipError_t launch_accept_tree_nodes_fast(const AcceptArgs &a, const int32_t *parents);
+hipError_t launch_accept_tree_walk(const AcceptArgs &a, int32_t *out_path);
 hipError_t launch_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,
                                   const int32_t *ctx_lens, const int32_t *spec_lens,
                                   const int32_t *out_path, const int32_t *out_accept_len,

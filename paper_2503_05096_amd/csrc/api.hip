@@ -306,8 +306,12 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
 {
     int rc = validate_accept_dims(dims);
     if (rc != ADASPEC_OK) return rc;
-    if (dims->path != ADASPEC_PATH_AUTO && dims->path != ADASPEC_PATH_VECTOR) return ADASPEC_ERR_UNSUPPORTED;
+    if (dims->path != ADASPEC_PATH_AUTO && dims->path != ADASPEC_PATH_VECTOR && dims->path != ADASPEC_PATH_FAST)
+        return ADASPEC_ERR_UNSUPPORTED;
     if (dims->max_spec_len > 63) return ADASPEC_ERR_UNSUPPORTED;
+    const bool fast_ok = accept_fast_path_supported(*dims, target_logits, draft_probs);
+    if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
+    const bool fast = fast_ok && dims->path != ADASPEC_PATH_VECTOR;
     if (dims->batch == 0) return ADASPEC_OK;
     if (!target_logits || !parents || !uniforms || !spec_lens || !temperature || !out_tokens ||
         !out_accept_len || !out_path || !workspace)
@@ -325,7 +329,9 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
     if (launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
-    if (launch_accept_tree(a, parents, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
+    if ((fast ? launch_accept_tree_nodes_fast(a, parents) : launch_accept_tree_nodes(a, parents)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    if (launch_accept_tree_walk(a, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     return ADASPEC_OK;

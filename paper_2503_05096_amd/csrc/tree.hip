@@ -310,7 +310,18 @@ __global__ __launch_bounds__(256) void accept_tree_walk_kernel(
     out_accept_len[i] = depth;
 }
 
-hipError_t launch_accept_tree(const AcceptArgs &a, const int32_t *parents, int32_t *out_path)
+hipError_t launch_accept_tree_walk(const AcceptArgs &a, int32_t *out_path)
+{
+    const adaspec_accept_dims &d = a.dims;
+    if (d.batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(accept_tree_walk_kernel, dim3(ceil_div(d.batch, 256)), dim3(256), 0, a.stream,
+                       a.spec_lens, a.draft_tokens, (const int32_t *)(a.ws + a.plan.off_cu_q),
+                       (const int32_t *)(a.ws + a.plan.off_row_flag), (const int32_t *)(a.ws + a.plan.off_row_cand),
+                       d.batch, d.total_q, d.max_spec_len, d.out_stride, a.out_tokens, a.out_accept_len, out_path);
+    return hipGetLastError();
+}
+
+hipError_t launch_accept_tree_nodes(const AcceptArgs &a, const int32_t *parents)
 {
     const adaspec_accept_dims &d = a.dims;
     if (d.total_q == 0) return hipSuccess;
@@ -333,10 +344,6 @@ hipError_t launch_accept_tree(const AcceptArgs &a, const int32_t *parents, int32
     if (d.logits_dtype == ADASPEC_F32) with_l(F32{});
     else if (d.logits_dtype == ADASPEC_F16) with_l(F16{});
     else with_l(BF16{});
-    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-    hipLaunchKernelGGL(accept_tree_walk_kernel, dim3(ceil_div(d.batch, 256)), dim3(256), 0, a.stream,
-                       a.spec_lens, a.draft_tokens, cu_q, node_next, row_cand, d.batch, d.total_q,
-                       d.max_spec_len, d.out_stride, a.out_tokens, a.out_accept_len, out_path);
     return hipGetLastError();
 }
 

@@ -253,7 +253,9 @@ def test_tree_calls_validate_on_the_host():
         p = [PTR] * 10
         p[k] = None
         assert tree_acc(a, p) == -1, k
-    assert tree_acc(_accept_dims(path=2), [PTR] * 10) == -6                 # only the portable kernel
+    assert tree_acc(_accept_dims(path=3), [PTR] * 10) == -6                 # no streaming / two-pass form for trees
+    assert tree_acc(_accept_dims(path=2, vocab=1001, logits_row_stride=1001, probs_row_stride=1001),
+                    [PTR] * 10) == -6                                       # the fast kernel needs V % 8 == 0
     assert tree_acc(_accept_dims(total_q=68, total_draft=66, max_spec_len=64, out_stride=65), [PTR] * 10) == -6
     assert tree_acc(_accept_dims(out_stride=3), [PTR] * 10) == -2
     assert tree_acc(a, [PTR] * 10, nbytes=16) == -5

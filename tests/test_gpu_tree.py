@@ -53,13 +53,13 @@ def _check_tree_attention(st, oracle, pkg, path="auto"):
     return rep
 
 
-def _check_tree_accept(st, oracle, pkg, out_stride=None, max_near_tie_frac=0.05):
+def _check_tree_accept(st, oracle, pkg, out_stride=None, max_near_tie_frac=0.05, kpath="auto"):
     import torch
     dev = to_device(st, attention=False)
-    _say(f"tree accept {st.name} B={st.batch} TQ={st.total_q} V={st.vocab}")
+    _say(f"tree accept {st.name} path={kpath} B={st.batch} TQ={st.total_q} V={st.vocab}")
     toks, alen, path = pkg.accept_tree(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.parents,
                                        dev.uniforms, dev.spec_lens, dev.temperature,
-                                       max_spec_len=st.max_spec_len, out_stride=out_stride)
+                                       max_spec_len=st.max_spec_len, out_stride=out_stride, path=kpath)
     torch.cuda.synchronize()
     rep = compare_accept_tree(st, toks.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), oracle,
                               out_stride=out_stride)
@@ -67,7 +67,8 @@ def _check_tree_accept(st, oracle, pkg, out_stride=None, max_near_tie_frac=0.05)
     assert rep["hard_mismatches"] == 0, rep["details"][:5]
     assert rep["ratio_near_ties"] + rep["cdf_near_ties"] <= max(2, max_near_tie_frac * st.batch), rep
     again = pkg.accept_tree(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.parents, dev.uniforms,
-                            dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len, out_stride=out_stride)
+                            dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len, out_stride=out_stride,
+                            path=kpath)
     torch.cuda.synchronize()
     assert all(torch.equal(a, b) for a, b in zip((toks, alen, path), again))
     return rep, (toks, alen, path)
@@ -122,11 +123,37 @@ def test_tree_attention_metadata_reuse(oracle_mod, pkg):
 
 
 # ----------------------------------------------------------------- acceptance
-@pytest.mark.parametrize("cfg,greedy,width", [(1, False, 2), (2, False, 3), (3, False, 3), (4, True, 3), (5, False, 2)])
+@pytest.mark.parametrize("cfg,greedy,width", [(1, False, 2), (2, False, 3), (3, False, 3), (4, False, 2),
+                                              (4, True, 3), (5, False, 2)])
 def test_config_tree_accept(cfg, greedy, width, oracle_mod, pkg):
+    """AUTO: the 1024-thread node kernel for the 16-bit configs, the portable one for config 1."""
     st = W.attach_tree(W.make_verify_step(cfg, greedy=greedy, attention=False), max_width=width)
     rep, _ = _check_tree_accept(st, oracle_mod, pkg)
     assert 0 < rep["oracle_mean_accept_len"]
+
+
+@pytest.mark.parametrize("cfg,width", [(2, 3), (3, 2)])
+def test_config_tree_accept_portable_kernel(cfg, width, oracle_mod, pkg):
+    st = W.attach_tree(W.make_verify_step(cfg, attention=False, batch=24), max_width=width)
+    _check_tree_accept(st, oracle_mod, pkg, kpath="vector")
+
+
+@pytest.mark.parametrize("dtype,V,sigma", [("bf16", 4096, 0.3), ("f16", 32000, 0.5), ("bf16", 131072, 0.6),
+                                           ("bf16", 8, 0.3)])
+def test_tree_accept_fast_kernel_shapes(dtype, V, sigma, oracle_mod, pkg):
+    """The 1024-thread kernel on vocabularies from one partial step to the sixteen steps it holds, with a
+    draft close enough to the target that later children get tested and long paths occur."""
+    rng = np.random.default_rng(8)
+    spec = np.array([0, 1, 8, 8, 20, 63, 3, 5, 12, 2, 7, 7, 30, 4], np.int32)
+    T = rng.choice([0.0, 0.6, 1.0, 1.4], size=spec.shape[0])
+    st = W.make_custom_step(321, ctx_lens=spec + 1, spec_lens=spec, vocab=V, logits_dtype=dtype, temperature=T,
+                            attention=False, noise_sigma=sigma, name=f"tree-fast-{dtype}-{V}")
+    W.attach_tree(st, max_width=4)
+    cu = st.cu_q
+    st.parents[cu[2] + 1:cu[3]] = 0                                  # request 2: a star of 8 children
+    rep, (toks, alen, path) = _check_tree_accept(st, oracle_mod, pkg, kpath="fast", max_near_tie_frac=0.2)
+    if V >= 4096:
+        assert alen.max().item() >= 2
 
 
 @pytest.mark.parametrize("dtype,V", [("f32", 1000), ("bf16", 4104), ("f16", 777)])
@@ -153,7 +180,7 @@ def test_chain_tree_accept_equals_the_chain_call(pkg):
     t1, a1 = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens,
                         dev.temperature, max_spec_len=st.max_spec_len, path="vector")
     t2, a2, p2 = pkg.accept_tree(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.parents, dev.uniforms,
-                                 dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len)
+                                 dev.spec_lens, dev.temperature, max_spec_len=st.max_spec_len, path="vector")
     torch.cuda.synchronize()
     assert torch.equal(t1, t2) and torch.equal(a1, a2)
     p2, a2 = p2.cpu().numpy(), a2.cpu().numpy()

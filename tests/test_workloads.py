@@ -144,3 +144,23 @@ def test_attach_tree_structure_and_determinism():
     W.attach_tree(st, chain=True)
     for i in range(st.batch):
         assert list(st.parents[cu[i]:cu[i + 1]]) == list(range(-1, int(st.spec_lens[i])))
+
+
+def test_tree_byte_accounting():
+    st = W.make_custom_step(5, ctx_lens=[9, 3, 30], spec_lens=[4, 0, 6], vocab=64, logits_dtype="bf16",
+                            attention=False, temperature=[1.0, 1.0, 0.0])
+    W.attach_tree(st, max_width=2)
+    has = W.tree_internal_nodes(st)
+    cu = st.cu_q
+    for i in range(st.batch):
+        par = st.parents[cu[i]:cu[i + 1]]
+        for u in range(len(par)):
+            assert has[cu[i] + u] == (u in set(par[1:]))
+        assert not has[cu[i + 1] - 1]                                   # the last node is a leaf
+    b = W.algorithmic_bytes_tree(st)
+    assert b["logits"] == st.total_q * 64 * 2
+    assert b["probs"] == int(has[cu[0]:cu[1]].sum()) * 64 * 2           # only request 0 is sampled and has drafts
+    assert b["accept"] == b["logits"] + b["probs"] == b["total"]
+    # a chain: every node but the last of each request has a child -> the per-row chain figure
+    W.attach_tree(st, chain=True)
+    assert W.algorithmic_bytes_tree(st) == W.algorithmic_bytes(st)

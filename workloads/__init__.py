@@ -18,5 +18,7 @@ from .verify_step import (  # noqa: F401
     bf16_bits_to_f32,
     to_f64,
     algorithmic_bytes,
+    algorithmic_bytes_tree,
+    tree_internal_nodes,
     accept_bytes_skipping_form,
 )

@@ -410,6 +410,31 @@ def algorithmic_bytes(st: VerifyStep) -> Dict[str, int]:
     return out
 
 
+def tree_internal_nodes(st: VerifyStep) -> np.ndarray:
+    """bool [TQ]: the node of this row has at least one child (needs st.parents)."""
+    cu = st.cu_q
+    has = np.zeros(st.total_q, dtype=bool)
+    for i in range(st.batch):
+        par = st.parents[cu[i] + 1:cu[i + 1]]
+        has[cu[i] + par] = True
+    return has
+
+
+def algorithmic_bytes_tree(st: VerifyStep) -> Dict[str, int]:
+    """As algorithmic_bytes, for a draft tree evaluated node by node: the attention moves the same
+    bytes (every node is a query row, its K/V row a cached token); the acceptance reads the logits
+    row of every node once, and the draft-probability row of every sampled (temperature > 0) node
+    that has children once."""
+    out = algorithmic_bytes(st)
+    if st.target_logits is not None:
+        psz = _ITEMSIZE[st.probs_dtype]
+        sampled_row = np.repeat(st.temperature != 0.0, st.spec_lens.astype(np.int64) + 1)
+        out["probs"] = int((tree_internal_nodes(st) & sampled_row).sum()) * st.vocab * psz
+        out["accept"] = out["logits"] + out["probs"]
+        out["total"] = out.get("attn", 0) + out["accept"]
+    return out
+
+
 def accept_bytes_skipping_form(st: VerifyStep, accept_len) -> Dict[str, int]:
     """Bytes of an acceptance that applies the sequential rule while it works (rows behind a
     request's first rejection are not read, and only the row that decides the request's token is
