@@ -5,12 +5,14 @@
 //   stage 0: P = softmax(logits / T); after each rejected child r = max(0, P - q), P = r / sum(r).
 // What differs is how the row is walked: 1024 threads, 16-byte loads, element (s * 1024 + t) * 8 + e
 // belongs to step s, thread t.  A "sweep" reads the logits row (and from stage 1 on the
-// draft-probability row) once and leaves, per thread, the fp32 sum of its 8 elements in every step
-// (seg[s]) and, per step, the fp64 total over the threads (S[s]); R = sum of the S[s].  A node
-// costs: one sweep for the maximum, one for the normaliser (= the stage-0 mass, unnormalised), one
-// per rejected child.  The draw needs no sweep of its own: the step where the prefix crosses comes
-// from S[], the thread from a scan over that step's seg values, and that thread alone loads its
-// 8 elements again.  The row is not kept in registers: later sweeps hit the caches.
+// draft-probability row) once and leaves, per step, the total mass S[s] (fp32 sums over the 128
+// elements of 16 neighbouring lanes, fp64 above that); R = sum of the S[s].  A node costs: one sweep
+// for the maximum, one for the normaliser (= the stage-0 mass, unnormalised), one per rejected
+// child.  The draw needs no sweep of its own: the step where the prefix crosses comes from S[];
+// the threads then load their 8 elements of that one step again, a scan over the threads finds
+// the one where the prefix crosses, and it picks the element.  The row is not kept in registers:
+// later sweeps hit the caches.  What a child's test needs (its token's logit, draft probability
+// and uniform) is fetched when the kernel starts, so a test is arithmetic on values already on chip.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"
@@ -28,8 +30,9 @@ struct NodeScratch {
     float  wmax[kNW];
     int    warg[kNW];
     double wsum[kNW];
-    double step_tot[kNW][kNSteps];
+    float  part[kNSteps][kWave];        // per step: fp32 sums of the 64 groups of 16 lanes (wave * 4 + lane / 16)
     double S[kNSteps];
+    float  ch_l[64], ch_q[64], ch_u[64];   // per child node: logit and draft probability of its token, its uniform
     float  inv_r[64];                   // 1 / R_s, s = 1 ..
     unsigned long long kept;            // bit s: stage s kept P_{s-1} (no positive part)
     unsigned long long kids;
@@ -37,7 +40,7 @@ struct NodeScratch {
 };
 
 template <class DT>
-__global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
+__global__ __launch_bounds__(kNT, 8) void accept_tree_node_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ parents,
     const float *__restrict__ uniforms, const int32_t *__restrict__ spec_lens,
@@ -57,10 +60,23 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
     const char *prow = probs + (int64_t)(r - i) * pstride * 2;   // read only if the node has children
     const int nsteps = ceil_div(V / 8, kNT);
 
+    auto elem16 = [](const char *row, int v) -> float {
+        const uint16_t b = reinterpret_cast<const uint16_t *>(row)[v];
+        return Pair16<DT>::lo((uint32_t)b);
+    };
+    // children of this node (lane c of the first wavefront looks at node c) and what their tests need
+    float pre_l = 0.f, pre_q = 0.f, pre_u = 0.f;
+    bool is_child = false;
     if (tid < kWave) {
-        const bool child = lane > u && lane <= k && sane_parent_f(parents[r0 + lane], lane) == u;
-        const unsigned long long kids = __builtin_amdgcn_ballot_w64(child);
+        is_child = lane > u && lane <= k && sane_parent_f(parents[r0 + lane], lane) == u;
+        const unsigned long long kids = __builtin_amdgcn_ballot_w64(is_child);
         if (lane == 0) { sm.kids = kids; sm.kept = 0ull; sm.hit = -1; sm.last_thread = -1; }
+        if (is_child) {
+            const int x = draft_tokens[r0 - i + lane - 1];
+            pre_l = elem16(lrow, x);
+            pre_q = elem16(prow, x);
+            pre_u = uniforms[2 * (int64_t)(r0 + lane - 1)];
+        }
     }
 
     auto unpack = [](const uint4 &w, float (&x)[8]) {
@@ -69,11 +85,6 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
         x[4] = Pair16<DT>::lo(w.z); x[5] = Pair16<DT>::hi(w.z);
         x[6] = Pair16<DT>::lo(w.w); x[7] = Pair16<DT>::hi(w.w);
     };
-    auto elem16 = [](const char *row, int v) -> float {
-        const uint16_t b = reinterpret_cast<const uint16_t *>(row)[v];
-        return Pair16<DT>::lo((uint32_t)b);
-    };
-
     // ---- sweep 1: maximum and its lowest index ------------------------------------------------
     ArgMax best{-INFINITY, V};
     for (int s = 0; s < nsteps; ++s) {
@@ -87,6 +98,7 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
     }
     best = wave_argmax(best);
     if (lane == 0) { sm.wmax[wv] = best.v; sm.warg[wv] = best.i; }
+    if (is_child) { sm.ch_l[lane] = pre_l; sm.ch_q[lane] = pre_q; sm.ch_u[lane] = pre_u; }
     __syncthreads();
     best = ArgMax{sm.wmax[0], sm.warg[0]};
 #pragma unroll
@@ -128,43 +140,47 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
         return keep_last ? P : fmaxf(0.f, P - q);
     };
 
-    float seg[kNSteps];
-    // One sweep: seg[] of every thread, S[] and the total.  stage 0: unnormalised 2^((l - m) c).
+    // the mass of this thread's 8 elements of step s at the given stage (0: unnormalised 2^((l - m) c))
+    auto step_mass = [&](int s, int s_stage, bool keep_last, const float (&inv)[kHoist],
+                         unsigned long long kept, float (&rv)[8]) -> float {
+        const int v0 = (s * kNT + tid) * 8;
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) rv[e] = 0.f;
+        if (v0 < V) {
+            float x[8];
+            unpack(*reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2), x);
+            if (s_stage == 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rv[e] = __builtin_amdgcn_exp2f((x[e] - m) * cexp);
+            } else {
+                float q[8];
+                unpack(*reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2), q);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rv[e] = mass(x[e], q[e], s_stage, keep_last, inv, kept);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += rv[e];
+        }
+        return acc;
+    };
+    // One sweep: S[] and the total.
     auto sweep = [&](int s_stage, bool keep_last) -> double {
         float inv[kHoist];
 #pragma unroll
         for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < s_stage) ? sm.inv_r[j + 1] : 1.0f;
         const unsigned long long kept = sm.kept;
-#pragma unroll
-        for (int s = 0; s < kNSteps; ++s) {
-            seg[s] = 0.f;
-            const int v0 = (s * kNT + tid) * 8;
-            if (s < nsteps && v0 < V) {
-                float x[8];
-                unpack(*reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2), x);
-                float acc = 0.f;
-                if (s_stage == 0) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f((x[e] - m) * cexp);
-                } else {
-                    float q[8];
-                    unpack(*reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2), q);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc += mass(x[e], q[e], s_stage, keep_last, inv, kept);
-                }
-                seg[s] = acc;
-            }
-            if (s < nsteps) {
-                const double ws = wave_sum((double)seg[s]);
-                if (lane == 0) sm.step_tot[wv][s] = ws;
-            }
+#pragma unroll 1
+        for (int s = 0; s < nsteps; ++s) {
+            float rv[8];
+            const float acc = row16_sum(step_mass(s, s_stage, keep_last, inv, kept, rv));
+            if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
         }
         __syncthreads();
-        if (tid < kNSteps) {
-            double t = 0.0;
-            if (tid < nsteps)
-                for (int w = 0; w < kNW; ++w) t += sm.step_tot[w][tid];
-            sm.S[tid] = t;
+        // wavefront s adds up the 64 partial sums of step s
+        {
+            const double t = wave_sum(wv < nsteps ? (double)sm.part[wv][lane] : 0.0);
+            if (lane == 0) sm.S[wv] = t;
         }
         __syncthreads();
         double R = 0.0;
@@ -183,18 +199,16 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
     while (kids != 0ull) {
         const int c = __builtin_ctzll(kids);
         kids &= kids - 1;
-        __syncthreads();                                        // the previous verdict has been read
-        if (tid == 0) {
-            const int x = draft_tokens[r0 - i + c - 1];
+        // every thread evaluates the test from the values fetched at the start: no exchange needed
+        {
             float inv[kHoist];
 #pragma unroll
             for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 <= stage) ? sm.inv_r[j + 1] : 1.0f;
-            const float qx = elem16(prow, x);
-            const float px = dist(elem16(lrow, x), qx, stage, inv, sm.kept);
-            sm.verdict = (qx > 0.f) ? (uniforms[2 * (int64_t)(r0 + c - 1)] < px / qx) : 1;
+            const float qx = sm.ch_q[c];
+            const float px = dist(sm.ch_l[c], qx, stage, inv, sm.kept);
+            const bool accepted = (qx > 0.f) ? (sm.ch_u[c] < px / qx) : true;
+            if (accepted) { next = c; break; }
         }
-        __syncthreads();
-        if (sm.verdict) { next = c; break; }
         ++stage;
         keep_last = false;
         R = sweep(stage, false);
@@ -202,16 +216,16 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
             keep_last = true;
             R = sweep(stage, true);
         }
-        if (tid == 0) {                                         // (sweep ended on a barrier; the next reader
-            sm.inv_r[stage] = (float)(1.0 / R);                 //  is behind the barrier at the loop's top or below)
+        if (tid == 0) {
+            sm.inv_r[stage] = (float)(1.0 / R);
             if (keep_last) sm.kept |= 1ull << stage;
         }
+        __syncthreads();
     }
     if (next >= 0) {
         if (tid == 0) { node_next[r] = next; row_cand[r] = best.i; }
         return;
     }
-    __syncthreads();
 
     // ---- the draw from (seg, S, R) of the last sweep ------------------------------------------
     const double tau = (double)uniforms[2 * (int64_t)r + 1] * R;
@@ -225,9 +239,15 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
         run += Ss;
     }
     if (sstar < 0) { sstar = last_pos_step; before = before_last; }   // rounding left no crossing
-    float mine = 0.f;
+    // this thread's 8 elements of that step, once more
+    float rv[8];
+    float mine;
+    {
+        float inv[kHoist];
 #pragma unroll
-    for (int s = 0; s < kNSteps; ++s) mine = (s == sstar) ? seg[s] : mine;
+        for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < stage) ? sm.inv_r[j + 1] : 1.0f;
+        mine = step_mass(sstar, stage, keep_last, inv, sm.kept, rv);
+    }
     // scan over the threads of that step
     const double wi = wave_scan_incl((double)mine, lane);
     double we = __shfl_up(wi, 1, kWave);
@@ -244,23 +264,16 @@ __global__ __launch_bounds__(kNT) void accept_tree_node_fast_kernel(
     // the crossing thread, and (in case rounding leaves none) the last thread with mass, look at their 8 elements
     if (crossing || tid == last_thread) {
         const int v0 = (sstar * kNT + tid) * 8;
-        float x[8], q[8], inv[kHoist];
-#pragma unroll
-        for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < stage) ? sm.inv_r[j + 1] : 1.0f;
-        unpack(*reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2), x);
-        if (stage > 0) unpack(*reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2), q);
         double cum = excl;
         int pick = -1, lastpos = -1;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float rv = stage == 0 ? __builtin_amdgcn_exp2f((x[e] - m) * cexp)
-                                        : mass(x[e], q[e], stage, keep_last, inv, sm.kept);
-            cum += (double)rv;
-            if (rv > 0.f) lastpos = v0 + e;
-            if (pick < 0 && cum > tau && rv > 0.f) pick = v0 + e;
+            cum += (double)rv[e];
+            if (rv[e] > 0.f) lastpos = v0 + e;
+            if (pick < 0 && cum > tau && rv[e] > 0.f) pick = v0 + e;
         }
         if (crossing) sm.hit = pick >= 0 ? pick : lastpos;
-        else if (tid == last_thread) sm.verdict = lastpos;       // fallback candidate
+        else sm.verdict = lastpos;                               // fallback candidate
     }
     __syncthreads();
     if (tid == 0) {
