@@ -188,7 +188,7 @@ def main() -> int:
         if tree:
             pkg.accept_tree(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.parents, dv.uniforms,
                             dv.spec_lens, dv.temperature, max_spec_len=kmax, out_tokens=toks,
-                            out_accept_len=alen, out_path=tpath_out, workspace=ws_acc, **kw)
+                            out_accept_len=alen, out_path=tpath_out, path=args.path, workspace=ws_acc, **kw)
         else:
             pkg.accept(dv.target_logits, dv.draft_probs, dv.draft_tokens, dv.uniforms, dv.spec_lens,
                        dv.temperature, max_spec_len=kmax, out_tokens=toks, out_accept_len=alen,
@@ -238,9 +238,13 @@ def main() -> int:
     # Which acceptance kernels ran decides what counts as algorithmic bytes: the per-row paths read every
     # logits row and every sampled draft-probability row; the two-pass path applies the sequential rule
     # while it works and never reads the rows it skips, so those bytes are not counted for it.
-    accept_path = "tree (per-node kernel)" if tree else pkg.accept_resolved_path(
+    accept_path = "tree (portable per-node kernel)" if tree else pkg.accept_resolved_path(
         dev0.target_logits, dev0.draft_probs, dev0.draft_tokens, dev0.spec_lens, max_spec_len=kmax, path=args.path)
     per_row_accept_bytes = nbytes["accept"]
+    if tree and args.path != "vector" and st.logits_dtype != "f32":
+        accept_path = "tree (node statistics + per-request walk)"
+        walk = W.tree_accept_bytes_walk_form(st, tpath_out.cpu().numpy(), alen.cpu().numpy())
+        nbytes = dict(nbytes, accept=walk["accept"], total=nbytes["attn"] + walk["accept"])
     if accept_path == "two_pass":
         skip = W.accept_bytes_skipping_form(st, alen.cpu().numpy())
         nbytes = dict(nbytes, accept=skip["accept"], total=nbytes["attn"] + skip["accept"])
@@ -319,7 +323,11 @@ def main() -> int:
                      "kernel_ms": spread(attn_all)},
         "roofline_accept": {"bound": "hbm",
                             "kernel": "acceptance kernels between the library's events (two-pass form: both passes)",
-                            "note": ("tree, per-node form: the logits row of every node once, and the draft-probability row "
+                            "note": ("tree, walk form: the logits row of every node once (statistics), and at the nodes a "
+                                     "walk reaches and rejects a child at, the logits and draft-probability rows once more; "
+                                     "nodes and rows the walk skips are NOT counted"
+                                     if tree and "walk" in accept_path else
+                                     "tree, per-node form: the logits row of every node once, and the draft-probability row "
                                      "of every sampled node that has children once"
                                      if tree else
                                      "two-pass form: algorithmic bytes = every draft row's logits row once (accept "

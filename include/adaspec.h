@@ -328,11 +328,14 @@ int adaspec_verify_attn_tree(const void *q, const void *k_pages, const void *v_p
  *   out_tokens     [B][out_stride]  tokens of the accepted nodes, the token emitted at the stop, then -1
  *   out_accept_len [B]              accepted nodes a_i
  *   out_path       [B][out_stride]  node indices of the accepted nodes in path order, then -1
- * Dims and workspace as for adaspec_accept.  Every node of every tree is evaluated, one workgroup
- * per node; dims->path: VECTOR = the portable kernel (any storage types and vocabulary size),
- * FAST = the 1024-thread kernel (same shapes as adaspec_accept's FAST), AUTO = FAST when it fits.
- * A node reads its logits row twice plus once, with its draft-probability row, per rejected child
- * (after the first read from the caches).
+ * Dims and workspace as for adaspec_accept.  dims->path:
+ *   VECTOR  the portable form (any storage types and vocabulary size): every node of every tree is
+ *           evaluated, one workgroup per node, then a small kernel walks the results;
+ *   FAST    same shapes as adaspec_accept's FAST: first the statistics of every node (two reads of its
+ *           logits row, the second from the caches), then one workgroup per request walks its tree
+ *           and reads, at the nodes it reaches only, the logits and draft-probability rows once per
+ *           rejected child;
+ *   AUTO    FAST when it fits, else VECTOR.
  */
 int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
                         const int32_t *draft_tokens, const int32_t *parents, const float *uniforms,

@@ -98,6 +98,7 @@ struct AcceptPlan {
     size_t off_req_pick;    // int2[B]: (deciding row, accepted drafts) of each request
     size_t off_half_stat;   // HalfStat[B][4]: per part of the row
     size_t off_part;        // float[B][16 steps][16][2][4]: partial sums of the split second pass (B <= kSplitMaxBatch)
+    size_t off_tree_stat;   // tree acceptance: per-node statistics (tree_node_stat_bytes() each)
     size_t total_bytes;
 };
 // p_v = 2^((l_v - m) c) / Z of a row (first pass of the two-pass form -> second pass)
@@ -138,10 +139,13 @@ size_t accept_split_part_bytes(int batch);
 hipError_t launch_accept_split(const AcceptArgs &a);
 
 // tree verification (tree.hip, tree_fast.hip): every node's acceptance, then the walk; needs the accept plan's cu_q / row_req
-// per-node kernels write (next node or -1, token if the walk stops here) into row_flag / row_cand:
-// the portable one (any types and sizes) and the 1024-thread one (shapes of the register-resident chain kernel)
+// portable form (any types and sizes): a per-node kernel writes (next node or -1, token if the walk stops here)
+// into row_flag / row_cand, a small kernel walks them
 hipError_t launch_accept_tree_nodes(const AcceptArgs &a, const int32_t *parents);
-hipError_t launch_accept_tree_nodes_fast(const AcceptArgs &a, const int32_t *parents);
+// 16-bit rows (shapes of the register-resident chain kernel): node statistics, then one workgroup per request
+// walks its tree and writes the outputs (no separate walk kernel)
+size_t tree_node_stat_bytes();
+hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, int32_t *out_path);
 hipError_t launch_accept_tree_walk(const AcceptArgs &a, int32_t *out_path);
 hipError_t launch_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,
                                   const int32_t *ctx_lens, const int32_t *spec_lens,

@@ -126,6 +126,7 @@ AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
     p.off_req_pick = off;  off = align_up(off + nb * sizeof(int2), 256);
     p.off_half_stat = off; off = align_up(off + nb * 4 * sizeof(HalfStat), 256);
     p.off_part = off;      off = align_up(off + (d.batch <= kSplitMaxBatch ? accept_split_part_bytes((int)nb) : 0), 256);
+    p.off_tree_stat = off; off = align_up(off + tq * tree_node_stat_bytes(), 256);
     p.total_bytes = off;
     return p;
 }
@@ -329,9 +330,12 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
     if (launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
-    if ((fast ? launch_accept_tree_nodes_fast(a, parents) : launch_accept_tree_nodes(a, parents)) != hipSuccess)
-        return ADASPEC_ERR_HIP;
-    if (launch_accept_tree_walk(a, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (fast) {
+        if (launch_accept_tree_fast(a, parents, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
+    } else {
+        if (launch_accept_tree_nodes(a, parents) != hipSuccess) return ADASPEC_ERR_HIP;
+        if (launch_accept_tree_walk(a, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
+    }
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     return ADASPEC_OK;

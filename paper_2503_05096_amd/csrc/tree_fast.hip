@@ -1,18 +1,25 @@
-// Tree acceptance of one node per workgroup, for 16-bit logits and draft probabilities of one
-// type, V % 8 == 0, V <= 131072 (the shapes of the register-resident chain kernel).
+// Tree acceptance for 16-bit logits and draft probabilities of one type, V % 8 == 0,
+// V <= 131072 (the shapes of the register-resident chain kernel), in two kernels:
 //
-// Same procedure and same per-element arithmetic as the portable node kernel (tree.hip):
+//   1. node statistics, one workgroup per node (= logits row): the maximum and its index, and
+//      for a sampled request the normaliser Z with its per-step parts S0[];
+//   2. the walk, one workgroup per request: from the root, at every node it reaches it tests
+//      the children in turn and, after each rejection, sweeps the node's logits and
+//      draft-probability rows once for the next residual mass; where the walk stops it draws
+//      the token.  It writes the request's outputs itself.
+// Nodes the walk does not reach cost their statistics only, and a node where the first child
+// is accepted never reads its draft-probability row.
+//
+// Same procedure and per-element arithmetic as the portable node kernel (tree.hip):
 //   stage 0: P = softmax(logits / T); after each rejected child r = max(0, P - q), P = r / sum(r).
-// What differs is how the row is walked: 1024 threads, 16-byte loads, element (s * 1024 + t) * 8 + e
-// belongs to step s, thread t.  A "sweep" reads the logits row (and from stage 1 on the
-// draft-probability row) once and leaves, per step, the total mass S[s] (fp32 sums over the 128
-// elements of 16 neighbouring lanes, fp64 above that); R = sum of the S[s].  A node costs: one sweep
-// for the maximum, one for the normaliser (= the stage-0 mass, unnormalised), one per rejected
-// child.  The draw needs no sweep of its own: the step where the prefix crosses comes from S[];
-// the threads then load their 8 elements of that one step again, a scan over the threads finds
-// the one where the prefix crosses, and it picks the element.  The row is not kept in registers:
-// later sweeps hit the caches.  What a child's test needs (its token's logit, draft probability
-// and uniform) is fetched when the kernel starts, so a test is arithmetic on values already on chip.
+// The row is walked by 1024 threads with 16-byte loads: element (s * 1024 + t) * 8 + e belongs
+// to step s, thread t.  A "sweep" leaves, per step, the total mass S[s] (fp32 sums over the 128
+// elements of 16 neighbouring lanes, fp64 above that); R = sum of the S[s].  The draw needs no
+// sweep of its own: the step where the prefix crosses comes from S[]; the threads then load
+// their 8 elements of that one step again, a scan over the threads finds the one where the
+// prefix crosses, and it picks the element.  What a child's test needs (its token, the token's
+// logit and draft probability, its uniform) is fetched when the walk arrives at the parent, so a
+// test is arithmetic on values already on chip.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"
@@ -26,102 +33,168 @@ constexpr int kHoist = 3;               // stages whose 1/R is kept in registers
 
 __device__ __forceinline__ int sane_parent_f(int p, int j) { return j == 0 ? -1 : min(max(p, 0), j - 1); }
 
-struct NodeScratch {
-    float  wmax[kNW];
-    int    warg[kNW];
-    double wsum[kNW];
+// what kernel 1 leaves per node
+struct TreeNodeStat {
+    float  m;               // maximum logit
+    int    arg;             // its lowest index
+    double Z;               // sum_v 2^((l_v - m) c) = sum of S0[]      (sampled requests only)
+    double S0[kNSteps];     // the same sum step by step
+};
+size_t tree_node_stat_bytes() { return sizeof(TreeNodeStat); }
+
+template <class DT>
+__device__ __forceinline__ void unpack8(const uint4 &w, float (&x)[8])
+{
+    x[0] = Pair16<DT>::lo(w.x); x[1] = Pair16<DT>::hi(w.x);
+    x[2] = Pair16<DT>::lo(w.y); x[3] = Pair16<DT>::hi(w.y);
+    x[4] = Pair16<DT>::lo(w.z); x[5] = Pair16<DT>::hi(w.z);
+    x[6] = Pair16<DT>::lo(w.w); x[7] = Pair16<DT>::hi(w.w);
+}
+template <class DT>
+__device__ __forceinline__ float elem16(const char *row, int v)
+{
+    return Pair16<DT>::lo((uint32_t) reinterpret_cast<const uint16_t *>(row)[v]);
+}
+
+// Per-step totals from the 64 partial sums each step left in `part`: wavefront s adds up step s.
+// Every thread returns R = sum of S[]; ends on a barrier.
+__device__ __forceinline__ double finish_sweep(const float (&part)[kNSteps][kWave], double (&S)[kNSteps],
+                                               int nsteps, int wv, int lane)
+{
+    __syncthreads();
+    {
+        const double t = wave_sum(wv < nsteps ? (double)part[wv][lane] : 0.0);
+        if (lane == 0) S[wv] = t;
+    }
+    __syncthreads();
+    double R = 0.0;
+#pragma unroll
+    for (int s = 0; s < kNSteps; ++s) R += S[s];
+    return R;
+}
+
+// Walks the steps of a row with the loads of the next kDepth steps in flight: f(step, in_range, logits
+// word, draft-probability word).  A wavefront that waited for every step's data before asking for the next
+// would pay one memory round trip per step.
+constexpr int kDepth = 4;
+template <bool kWithProbs, class F>
+__device__ __forceinline__ void for_each_step(const char *lrow, const char *prow, int nsteps, int V, int tid, F f)
+{
+    uint4 lw[kDepth], qw[kDepth];
+    auto issue = [&](int j, int s) {
+        const int v0 = (s * kNT + tid) * 8;
+        if (s < nsteps && v0 < V) {
+            lw[j] = *reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2);
+            if (kWithProbs) qw[j] = *reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < kDepth; ++j) { lw[j] = make_uint4(0, 0, 0, 0); qw[j] = make_uint4(0, 0, 0, 0); issue(j, j); }
+    for (int s0 = 0; s0 < nsteps; s0 += kDepth) {
+#pragma unroll
+        for (int j = 0; j < kDepth; ++j) {
+            const int s = s0 + j;
+            if (s < nsteps) {
+                f(s, (s * kNT + tid) * 8 < V, lw[j], qw[j]);
+                issue(j, s + kDepth);
+            }
+        }
+    }
+}
+
+// ---- kernel 1: statistics of every node ---------------------------------------------------------
+template <class DT>
+__global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
+    const char *__restrict__ logits, const float *__restrict__ temperature,
+    const int32_t *__restrict__ row_req, int B, int V, int64_t lstride, TreeNodeStat *__restrict__ stats)
+{
+    __shared__ float wmax[kNW];
+    __shared__ int warg[kNW];
+    __shared__ float part[kNSteps][kWave];
+    __shared__ double S[kNSteps];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r = blockIdx.x;
+    const float T = temperature[min(max(row_req[r], 0), B - 1)];
+    const char *lrow = logits + (int64_t)r * lstride * 2;
+    const int nsteps = ceil_div(V / 8, kNT);
+
+    ArgMax best{-INFINITY, V};
+    for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
+        if (!in_range) return;
+        const int v0 = (s * kNT + tid) * 8;
+        float x[8];
+        unpack8<DT>(lw, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
+    });
+    best = wave_argmax(best);
+    if (lane == 0) { wmax[wv] = best.v; warg[wv] = best.i; }
+    __syncthreads();
+    best = ArgMax{wmax[0], warg[0]};
+#pragma unroll
+    for (int w = 1; w < kNW; ++w) best = argmax_merge(best, ArgMax{wmax[w], warg[w]});
+    if (best.i >= V) best.i = 0;
+    TreeNodeStat *st = stats + r;
+    if (T == 0.0f) {                                            // greedy: the arg-max is all the walk needs
+        if (tid == 0) { st->m = best.v; st->arg = best.i; st->Z = 1.0; }
+        return;
+    }
+    const float m = best.v, cexp = 1.4426950408889634f / T;
+    for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
+        float acc = 0.f;
+        if (in_range) {
+            float x[8];
+            unpack8<DT>(lw, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f((x[e] - m) * cexp);
+        }
+        acc = row16_sum(acc);
+        if ((lane & 15) == 0) part[s][wv * 4 + (lane >> 4)] = acc;
+    });
+    const double Z = finish_sweep(part, S, nsteps, wv, lane);
+    if (tid == 0) { st->m = m; st->arg = best.i; st->Z = Z; }
+    if (tid < kNSteps) st->S0[tid] = tid < nsteps ? S[tid] : 0.0;
+}
+
+// ---- kernel 2: the walk of every request ---------------------------------------------------------
+struct WalkScratch {
     float  part[kNSteps][kWave];        // per step: fp32 sums of the 64 groups of 16 lanes (wave * 4 + lane / 16)
     double S[kNSteps];
+    double wsum[kNW];
     float  ch_l[64], ch_q[64], ch_u[64];   // per child node: logit and draft probability of its token, its uniform
+    int    ch_x[64];                    // its token
     float  inv_r[64];                   // 1 / R_s, s = 1 ..
     unsigned long long kept;            // bit s: stage s kept P_{s-1} (no positive part)
     unsigned long long kids;
-    int verdict, hit, last_thread;
+    int fallback, hit, last_thread;
 };
 
 template <class DT>
-__global__ __launch_bounds__(kNT, 8) void accept_tree_node_fast_kernel(
+__global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ parents,
     const float *__restrict__ uniforms, const int32_t *__restrict__ spec_lens,
     const float *__restrict__ temperature, const int32_t *__restrict__ cu_q,
-    const int32_t *__restrict__ row_req, int V, int max_spec_len, int64_t lstride, int64_t pstride,
-    int32_t *__restrict__ node_next, int32_t *__restrict__ row_cand)
+    const TreeNodeStat *__restrict__ stats, int V, int total_q, int max_spec_len, int64_t lstride,
+    int64_t pstride, int out_stride, int32_t *__restrict__ out_tokens,
+    int32_t *__restrict__ out_accept_len, int32_t *__restrict__ out_path)
 {
-    __shared__ NodeScratch sm;
+    __shared__ WalkScratch sm;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int r = blockIdx.x;
-    const int i = row_req[r];
+    const int i = blockIdx.x;
     const int r0 = cu_q[i];
-    const int u = r - r0;
     const int k = min(max(spec_lens[i], 0), max_spec_len);
+    if (r0 < 0 || r0 + k + 1 > total_q) return;                 // inconsistent metadata: leave the request alone
     const float T = temperature[i];
-    const char *lrow = logits + (int64_t)r * lstride * 2;
-    const char *prow = probs + (int64_t)(r - i) * pstride * 2;   // read only if the node has children
+    const float cexp = T == 0.0f ? 0.f : 1.4426950408889634f / T;
     const int nsteps = ceil_div(V / 8, kNT);
+    int32_t *o = out_tokens + (int64_t)i * out_stride;
+    int32_t *pth = out_path + (int64_t)i * out_stride;
 
-    auto elem16 = [](const char *row, int v) -> float {
-        const uint16_t b = reinterpret_cast<const uint16_t *>(row)[v];
-        return Pair16<DT>::lo((uint32_t)b);
-    };
-    // children of this node (lane c of the first wavefront looks at node c) and what their tests need
-    float pre_l = 0.f, pre_q = 0.f, pre_u = 0.f;
-    bool is_child = false;
-    if (tid < kWave) {
-        is_child = lane > u && lane <= k && sane_parent_f(parents[r0 + lane], lane) == u;
-        const unsigned long long kids = __builtin_amdgcn_ballot_w64(is_child);
-        if (lane == 0) { sm.kids = kids; sm.kept = 0ull; sm.hit = -1; sm.last_thread = -1; }
-        if (is_child) {
-            const int x = draft_tokens[r0 - i + lane - 1];
-            pre_l = elem16(lrow, x);
-            pre_q = elem16(prow, x);
-            pre_u = uniforms[2 * (int64_t)(r0 + lane - 1)];
-        }
-    }
-
-    auto unpack = [](const uint4 &w, float (&x)[8]) {
-        x[0] = Pair16<DT>::lo(w.x); x[1] = Pair16<DT>::hi(w.x);
-        x[2] = Pair16<DT>::lo(w.y); x[3] = Pair16<DT>::hi(w.y);
-        x[4] = Pair16<DT>::lo(w.z); x[5] = Pair16<DT>::hi(w.z);
-        x[6] = Pair16<DT>::lo(w.w); x[7] = Pair16<DT>::hi(w.w);
-    };
-    // ---- sweep 1: maximum and its lowest index ------------------------------------------------
-    ArgMax best{-INFINITY, V};
-    for (int s = 0; s < nsteps; ++s) {
-        const int v0 = (s * kNT + tid) * 8;
-        if (v0 >= V) break;
-        float x[8];
-        unpack(*reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2), x);
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
-    }
-    best = wave_argmax(best);
-    if (lane == 0) { sm.wmax[wv] = best.v; sm.warg[wv] = best.i; }
-    if (is_child) { sm.ch_l[lane] = pre_l; sm.ch_q[lane] = pre_q; sm.ch_u[lane] = pre_u; }
-    __syncthreads();
-    best = ArgMax{sm.wmax[0], sm.warg[0]};
-#pragma unroll
-    for (int w = 1; w < kNW; ++w) best = argmax_merge(best, ArgMax{sm.wmax[w], sm.warg[w]});
-    if (best.i >= V) best.i = 0;
-    unsigned long long kids = sm.kids;
-
-    if (T == 0.0f) {
-        if (tid == 0) {
-            int next = -1;
-            while (kids != 0ull && next < 0) {
-                const int c = __builtin_ctzll(kids);
-                kids &= kids - 1;
-                if (draft_tokens[r0 - i + c - 1] == best.i) next = c;
-            }
-            node_next[r] = next;
-            row_cand[r] = best.i;
-        }
-        return;
-    }
-    const float m = best.v;
-    const float cexp = 1.4426950408889634f / T;
-    float invZ = 1.0f;
+    // state of the node the walk stands on
+    const char *lrow = logits, *prow = probs;
+    float m = 0.f, invZ = 1.f;
 
     // P_s at one entry from its logit and draft probability (s >= 0); inv[] = hoisted 1/R_1..
     auto dist = [&](float l, float q, int s, const float (&inv)[kHoist], unsigned long long kept) -> float {
@@ -133,169 +206,202 @@ __global__ __launch_bounds__(kNT, 8) void accept_tree_node_fast_kernel(
             P = (((kept >> j) & 1ull) ? P : fmaxf(0.f, P - q)) * sm.inv_r[j];
         return P;
     };
-    // r_s at one entry (s >= 1); keep_last: stage s keeps P_{s-1}
-    auto mass = [&](float l, float q, int s, bool keep_last, const float (&inv)[kHoist],
-                    unsigned long long kept) -> float {
-        const float P = dist(l, q, s - 1, inv, kept);
-        return keep_last ? P : fmaxf(0.f, P - q);
-    };
-
-    // the mass of this thread's 8 elements of step s at the given stage (0: unnormalised 2^((l - m) c))
-    auto step_mass = [&](int s, int s_stage, bool keep_last, const float (&inv)[kHoist],
-                         unsigned long long kept, float (&rv)[8]) -> float {
-        const int v0 = (s * kNT + tid) * 8;
+    // this thread's 8 masses of one step at the given stage, from the loaded words; stage 0: unnormalised
+    // 2^((l - m) c); stage >= 1: r = max(0, P_{stage-1} - q), or P_{stage-1} itself if the stage keeps it
+    auto mass8 = [&](bool in_range, const uint4 &lw, const uint4 &qw, int s_stage, bool keep_last,
+                     const float (&inv)[kHoist], unsigned long long kept, float (&rv)[8]) -> float {
         float acc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) rv[e] = 0.f;
-        if (v0 < V) {
+        if (in_range) {
             float x[8];
-            unpack(*reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2), x);
+            unpack8<DT>(lw, x);
             if (s_stage == 0) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) rv[e] = __builtin_amdgcn_exp2f((x[e] - m) * cexp);
             } else {
                 float q[8];
-                unpack(*reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2), q);
+                unpack8<DT>(qw, q);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) rv[e] = mass(x[e], q[e], s_stage, keep_last, inv, kept);
+                for (int e = 0; e < 8; ++e) {
+                    const float P = dist(x[e], q[e], s_stage - 1, inv, kept);
+                    rv[e] = keep_last ? P : fmaxf(0.f, P - q[e]);
+                }
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc += rv[e];
         }
         return acc;
     };
-    // One sweep: S[] and the total.
+    // one sweep at stage >= 1 (both rows)
     auto sweep = [&](int s_stage, bool keep_last) -> double {
         float inv[kHoist];
 #pragma unroll
         for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < s_stage) ? sm.inv_r[j + 1] : 1.0f;
         const unsigned long long kept = sm.kept;
-#pragma unroll 1
-        for (int s = 0; s < nsteps; ++s) {
+        for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
             float rv[8];
-            const float acc = row16_sum(step_mass(s, s_stage, keep_last, inv, kept, rv));
+            const float acc = row16_sum(mass8(in_range, lw, qw, s_stage, keep_last, inv, kept, rv));
             if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
-        }
-        __syncthreads();
-        // wavefront s adds up the 64 partial sums of step s
-        {
-            const double t = wave_sum(wv < nsteps ? (double)sm.part[wv][lane] : 0.0);
-            if (lane == 0) sm.S[wv] = t;
-        }
-        __syncthreads();
-        double R = 0.0;
-#pragma unroll
-        for (int s = 0; s < kNSteps; ++s) R += sm.S[s];
-        return R;
+        });
+        return finish_sweep(sm.part, sm.S, nsteps, wv, lane);
     };
 
-    // ---- sweep 2: the normaliser (= total of the stage-0 mass) ---------------------------------
-    double R = sweep(0, false);
-    invZ = (float)(1.0 / R);
-
-    // ---- the children, one after another -------------------------------------------------------
-    int next = -1, stage = 0;
-    bool keep_last = false;
-    while (kids != 0ull) {
-        const int c = __builtin_ctzll(kids);
-        kids &= kids - 1;
-        // every thread evaluates the test from the values fetched at the start: no exchange needed
-        {
-            float inv[kHoist];
-#pragma unroll
-            for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 <= stage) ? sm.inv_r[j + 1] : 1.0f;
-            const float qx = sm.ch_q[c];
-            const float px = dist(sm.ch_l[c], qx, stage, inv, sm.kept);
-            const bool accepted = (qx > 0.f) ? (sm.ch_u[c] < px / qx) : true;
-            if (accepted) { next = c; break; }
+    int u = 0, depth = 0;
+    for (;;) {
+        const int r = r0 + u;
+        lrow = logits + (int64_t)r * lstride * 2;
+        prow = probs + (int64_t)(r - i) * pstride * 2;          // read only if the node has children
+        const TreeNodeStat *st = stats + r;
+        __syncthreads();                                        // everything of the previous node has been read
+        // children of u (lane c of the first wavefront looks at node c) and what their tests need
+        if (tid < kWave) {
+            const bool is_child = lane > u && lane <= k && sane_parent_f(parents[r0 + lane], lane) == u;
+            const unsigned long long kmask = __builtin_amdgcn_ballot_w64(is_child);
+            if (lane == 0) { sm.kids = kmask; sm.kept = 0ull; sm.hit = -1; sm.last_thread = -1; sm.fallback = -1; }
+            if (is_child) {
+                const int x = draft_tokens[r0 - i + lane - 1];
+                sm.ch_x[lane] = x;
+                sm.ch_l[lane] = elem16<DT>(lrow, x);
+                sm.ch_q[lane] = elem16<DT>(prow, x);
+                sm.ch_u[lane] = uniforms[2 * (int64_t)(r0 + lane - 1)];
+            }
+        } else if (tid < kWave + kNSteps) {
+            sm.S[tid - kWave] = st->S0[tid - kWave];
         }
-        ++stage;
-        keep_last = false;
-        R = sweep(stage, false);
-        if (!(R > 0.0)) {                                       // P == q everywhere: the state stays
-            keep_last = true;
-            R = sweep(stage, true);
-        }
-        if (tid == 0) {
-            sm.inv_r[stage] = (float)(1.0 / R);
-            if (keep_last) sm.kept |= 1ull << stage;
-        }
+        m = st->m;
+        const int arg = st->arg;
+        double R = st->Z;
+        invZ = (float)(1.0 / R);
         __syncthreads();
-    }
-    if (next >= 0) {
-        if (tid == 0) { node_next[r] = next; row_cand[r] = best.i; }
-        return;
-    }
+        unsigned long long kids = sm.kids;
 
-    // ---- the draw from (seg, S, R) of the last sweep ------------------------------------------
-    const double tau = (double)uniforms[2 * (int64_t)r + 1] * R;
-    int sstar = -1, last_pos_step = 0;
-    double before = 0.0, run = 0.0, before_last = 0.0;
+        int next = -1, cand = arg;
+        if (T == 0.0f) {
+            // greedy: the first child that carries the target's arg-max, else stop with the arg-max
+            while (kids != 0ull && next < 0) {
+                const int c = __builtin_ctzll(kids);
+                kids &= kids - 1;
+                if (sm.ch_x[c] == arg) next = c;
+            }
+        } else {
+            int stage = 0;
+            bool keep_last = false;
+            while (kids != 0ull) {
+                const int c = __builtin_ctzll(kids);
+                kids &= kids - 1;
+                {   // every thread evaluates the test from the values fetched on arrival: no exchange needed
+                    float inv[kHoist];
 #pragma unroll
-    for (int s = 0; s < kNSteps; ++s) {
-        const double Ss = sm.S[s];
-        if (Ss > 0.0) { last_pos_step = s; before_last = run; }
-        if (sstar < 0 && run + Ss > tau) { sstar = s; before = run; }
-        run += Ss;
-    }
-    if (sstar < 0) { sstar = last_pos_step; before = before_last; }   // rounding left no crossing
-    // this thread's 8 elements of that step, once more
-    float rv[8];
-    float mine;
-    {
-        float inv[kHoist];
+                    for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 <= stage) ? sm.inv_r[j + 1] : 1.0f;
+                    const float qx = sm.ch_q[c];
+                    const float px = dist(sm.ch_l[c], qx, stage, inv, sm.kept);
+                    const bool accepted = (qx > 0.f) ? (sm.ch_u[c] < px / qx) : true;
+                    if (accepted) { next = c; break; }
+                }
+                ++stage;
+                keep_last = false;
+                R = sweep(stage, false);
+                if (!(R > 0.0)) {                               // P == q everywhere: the state stays
+                    keep_last = true;
+                    R = sweep(stage, true);
+                }
+                if (tid == 0) {
+                    sm.inv_r[stage] = (float)(1.0 / R);
+                    if (keep_last) sm.kept |= 1ull << stage;
+                }
+                __syncthreads();
+            }
+            if (next < 0) {
+                // ---- the draw from (S, R): of the last sweep, or at stage 0 of the node's statistics ----
+                const double tau = (double)uniforms[2 * (int64_t)r + 1] * R;
+                int sstar = -1, last_pos_step = 0;
+                double before = 0.0, run = 0.0, before_last = 0.0;
 #pragma unroll
-        for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < stage) ? sm.inv_r[j + 1] : 1.0f;
-        mine = step_mass(sstar, stage, keep_last, inv, sm.kept, rv);
-    }
-    // scan over the threads of that step
-    const double wi = wave_scan_incl((double)mine, lane);
-    double we = __shfl_up(wi, 1, kWave);
-    if (lane == 0) we = 0.0;
-    if (lane == 63) sm.wsum[wv] = wi;
-    if (mine > 0.f) atomicMax(&sm.last_thread, tid);
-    __syncthreads();
-    double wp = 0.0;
+                for (int s = 0; s < kNSteps; ++s) {
+                    const double Ss = sm.S[s];
+                    if (Ss > 0.0) { last_pos_step = s; before_last = run; }
+                    if (sstar < 0 && run + Ss > tau) { sstar = s; before = run; }
+                    run += Ss;
+                }
+                if (sstar < 0) { sstar = last_pos_step; before = before_last; }   // rounding left no crossing
+                float rv[8];
+                float mine;
+                {
+                    float inv[kHoist];
 #pragma unroll
-    for (int w = 0; w < kNW; ++w) wp += (w < wv) ? sm.wsum[w] : 0.0;
-    const double excl = before + wp + we, incl = before + wp + wi;
-    const bool crossing = incl > tau && !(excl > tau);
-    const int last_thread = sm.last_thread;
-    // the crossing thread, and (in case rounding leaves none) the last thread with mass, look at their 8 elements
-    if (crossing || tid == last_thread) {
-        const int v0 = (sstar * kNT + tid) * 8;
-        double cum = excl;
-        int pick = -1, lastpos = -1;
+                    for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < stage) ? sm.inv_r[j + 1] : 1.0f;
+                    const int v0 = (sstar * kNT + tid) * 8;
+                    uint4 lw = make_uint4(0, 0, 0, 0), qw = make_uint4(0, 0, 0, 0);
+                    if (v0 < V) {
+                        lw = *reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2);
+                        if (stage > 0) qw = *reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2);
+                    }
+                    mine = mass8(v0 < V, lw, qw, stage, keep_last, inv, sm.kept, rv);
+                }
+                // scan over the threads of that step
+                const double wi = wave_scan_incl((double)mine, lane);
+                double we = __shfl_up(wi, 1, kWave);
+                if (lane == 0) we = 0.0;
+                if (lane == 63) sm.wsum[wv] = wi;
+                if (mine > 0.f) atomicMax(&sm.last_thread, tid);
+                __syncthreads();
+                double wp = 0.0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            cum += (double)rv[e];
-            if (rv[e] > 0.f) lastpos = v0 + e;
-            if (pick < 0 && cum > tau && rv[e] > 0.f) pick = v0 + e;
+                for (int w = 0; w < kNW; ++w) wp += (w < wv) ? sm.wsum[w] : 0.0;
+                const double excl = before + wp + we, incl = before + wp + wi;
+                const bool crossing = incl > tau && !(excl > tau);
+                const int last_thread = sm.last_thread;
+                // the crossing thread, and (in case rounding leaves none) the last thread with mass
+                if (crossing || tid == last_thread) {
+                    const int v0 = (sstar * kNT + tid) * 8;
+                    double cum = excl;
+                    int pick = -1, lastpos = -1;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        cum += (double)rv[e];
+                        if (rv[e] > 0.f) lastpos = v0 + e;
+                        if (pick < 0 && cum > tau && rv[e] > 0.f) pick = v0 + e;
+                    }
+                    if (crossing) sm.hit = pick >= 0 ? pick : lastpos;
+                    else sm.fallback = lastpos;
+                }
+                __syncthreads();
+                cand = sm.hit;
+                if (cand < 0) cand = sm.fallback;
+                if (cand < 0) cand = arg;
+            }
         }
-        if (crossing) sm.hit = pick >= 0 ? pick : lastpos;
-        else sm.verdict = lastpos;                               // fallback candidate
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int cand = sm.hit;
-        if (cand < 0) cand = last_thread >= 0 ? sm.verdict : best.i;
-        node_next[r] = -1;
-        row_cand[r] = cand;
+        if (next < 0) {                                         // the walk stops here
+            if (tid == 0) {
+                o[depth] = cand;
+                pth[depth] = -1;
+                out_accept_len[i] = depth;
+            }
+            for (int j = depth + 1 + tid; j < out_stride; j += kNT) { o[j] = -1; pth[j] = -1; }
+            return;
+        }
+        if (tid == 0) { o[depth] = sm.ch_x[next]; pth[depth] = next; }
+        ++depth;
+        u = next;
     }
 }
 
-hipError_t launch_accept_tree_nodes_fast(const AcceptArgs &a, const int32_t *parents)
+hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, int32_t *out_path)
 {
     const adaspec_accept_dims &d = a.dims;
     if (d.total_q == 0) return hipSuccess;
+    TreeNodeStat *stats = (TreeNodeStat *)(a.ws + a.plan.off_tree_stat);
     auto launch = [&](auto tag) {
         using DT = decltype(tag);
-        hipLaunchKernelGGL((accept_tree_node_fast_kernel<DT>), dim3(d.total_q), dim3(kNT), 0, a.stream,
+        hipLaunchKernelGGL((tree_node_stats_kernel<DT>), dim3(d.total_q), dim3(kNT), 0, a.stream,
+                           (const char *)a.logits, a.temperature, (const int32_t *)(a.ws + a.plan.off_row_req),
+                           d.batch, d.vocab, d.logits_row_stride, stats);
+        hipLaunchKernelGGL((accept_tree_walk_fast_kernel<DT>), dim3(d.batch), dim3(kNT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, parents, a.uniforms,
-                           a.spec_lens, a.temperature, (const int32_t *)(a.ws + a.plan.off_cu_q),
-                           (const int32_t *)(a.ws + a.plan.off_row_req), d.vocab, d.max_spec_len,
-                           d.logits_row_stride, d.probs_row_stride, (int32_t *)(a.ws + a.plan.off_row_flag),
-                           (int32_t *)(a.ws + a.plan.off_row_cand));
+                           a.spec_lens, a.temperature, (const int32_t *)(a.ws + a.plan.off_cu_q), stats, d.vocab,
+                           d.total_q, d.max_spec_len, d.logits_row_stride, d.probs_row_stride, d.out_stride,
+                           a.out_tokens, a.out_accept_len, out_path);
     };
     if (d.logits_dtype == ADASPEC_F16) launch(F16{});
     else launch(BF16{});

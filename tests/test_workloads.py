@@ -164,3 +164,19 @@ def test_tree_byte_accounting():
     # a chain: every node but the last of each request has a child -> the per-row chain figure
     W.attach_tree(st, chain=True)
     assert W.algorithmic_bytes_tree(st) == W.algorithmic_bytes(st)
+
+
+def test_tree_walk_form_bytes():
+    st = W.make_custom_step(6, ctx_lens=[9, 9, 9], spec_lens=[3, 3, 2], vocab=16, logits_dtype="bf16",
+                            attention=False, temperature=[1.0, 1.0, 0.0])
+    st.parents = np.array([-1, 0, 0, 1,   -1, 0, 1, 2,   -1, 0, 0], np.int32)
+    # request 0: root has children 1, 2; walk accepts 2 (child 1 rejected: root rejects), node 2 is a leaf
+    # request 1: a chain; walk accepts 1, then stops at node 1 (its child rejected)
+    # request 2: greedy: nothing beyond the statistics
+    path = np.array([[2, -1, -1, -1], [1, -1, -1, -1], [-1, -1, -1, -1]], np.int32)
+    b = W.tree_accept_bytes_walk_form(st, path, np.array([1, 1, 0]))
+    assert b["rejecting_nodes_on_walks"] == 2
+    assert b["stats_logits"] == 11 * 16 * 2 and b["walk_rows"] == 2 * 16 * 4 and b["accept"] == b["stats_logits"] + b["walk_rows"]
+    # first children accepted all the way down to a leaf: no rejecting node
+    path = np.array([[1, 3, -1, -1], [1, 2, 3, -1], [-1, -1, -1, -1]], np.int32)
+    assert W.tree_accept_bytes_walk_form(st, path, np.array([2, 3, 0]))["rejecting_nodes_on_walks"] == 0

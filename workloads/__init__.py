@@ -20,5 +20,6 @@ from .verify_step import (  # noqa: F401
     algorithmic_bytes,
     algorithmic_bytes_tree,
     tree_internal_nodes,
+    tree_accept_bytes_walk_form,
     accept_bytes_skipping_form,
 )

@@ -435,6 +435,33 @@ def algorithmic_bytes_tree(st: VerifyStep) -> Dict[str, int]:
     return out
 
 
+def tree_accept_bytes_walk_form(st: VerifyStep, path, accept_len) -> Dict[str, int]:
+    """Bytes of a tree acceptance that walks while it works: the logits row of every node once (its
+    maximum, arg-max and normaliser); then, only at the nodes the walk reaches and only if at least
+    one child is rejected there, the logits row and the draft-probability row once more (all residual
+    stages of a node are functions of these two rows).  Greedy requests stop at the first part.
+    `path[i]`, `accept_len[i]`: the acceptance's own outputs (node indices of the accepted nodes)."""
+    lsz, psz = _ITEMSIZE[st.logits_dtype], _ITEMSIZE[st.probs_dtype]
+    cu = st.cu_q
+    path = np.asarray(path)
+    a = np.asarray(accept_len).astype(np.int64)
+    rejecting = 0
+    for i in range(st.batch):
+        if st.temperature[i] == 0.0:
+            continue
+        par = st.parents[cu[i]:cu[i + 1]]
+        walk = [0] + [int(x) for x in path[i, :a[i]]]
+        for d, u in enumerate(walk):
+            kids = np.nonzero(par[1:] == u)[0] + 1
+            nxt = walk[d + 1] if d + 1 < len(walk) else None
+            if (nxt is None and kids.size) or (nxt is not None and (kids < nxt).any()):
+                rejecting += 1
+    stats = st.total_q * st.vocab * lsz
+    resid = rejecting * st.vocab * (lsz + psz)
+    return {"stats_logits": stats, "walk_rows": resid, "rejecting_nodes_on_walks": rejecting,
+            "accept": stats + resid}
+
+
 def accept_bytes_skipping_form(st: VerifyStep, accept_len) -> Dict[str, int]:
     """Bytes of an acceptance that applies the sequential rule while it works (rows behind a
     request's first rejection are not read, and only the row that decides the request's token is
