@@ -1,8 +1,8 @@
 // Tree acceptance for 16-bit logits and draft probabilities of one type, V % 8 == 0,
 // V <= 131072 (the shapes of the register-resident chain kernel), in two kernels:
 //
-//   1. node statistics, one workgroup per node (= logits row): the maximum and its index, and
-//      for a sampled request the normaliser Z with its per-step parts S0[];
+//   1. node statistics, one workgroup per node (= logits row), one read of the row: the maximum
+//      and its index, and for a sampled request the normaliser Z with its per-step parts S0[];
 //   2. the walk, one workgroup per request: from the root, at every node it reaches it tests
 //      the children in turn and, after each rejection, sweeps the node's logits and
 //      draft-probability rows once for the next residual mass; where the walk stops it draws
@@ -103,6 +103,10 @@ __device__ __forceinline__ void for_each_step(const char *lrow, const char *prow
 }
 
 // ---- kernel 1: statistics of every node ---------------------------------------------------------
+// ONE read of the row.  The sums of a step are taken relative to the maximum of the 128 elements of
+// each 16-lane group (known as soon as the group's loads are there) and put on the row's maximum at
+// the end: S0[s] = sum_g part[s][g] * 2^((gmax[s][g] - m) c).  A sampled row costs one exponential
+// per element, as a second sweep would, but the row is not fetched a second time.
 template <class DT>
 __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     const char *__restrict__ logits, const float *__restrict__ temperature,
@@ -110,23 +114,39 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
 {
     __shared__ float wmax[kNW];
     __shared__ int warg[kNW];
-    __shared__ float part[kNSteps][kWave];
+    __shared__ float part[kNSteps][kWave], gmax[kNSteps][kWave];
     __shared__ double S[kNSteps];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = blockIdx.x;
     const float T = temperature[min(max(row_req[r], 0), B - 1)];
     const char *lrow = logits + (int64_t)r * lstride * 2;
     const int nsteps = ceil_div(V / 8, kNT);
+    const bool sampled = T != 0.0f;
+    const float cexp = sampled ? 1.4426950408889634f / T : 0.f;
+    constexpr float kLowest = -3.0e38f;                          // stands in for -inf: differences stay defined
 
     ArgMax best{-INFINITY, V};
     for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
-        if (!in_range) return;
-        const int v0 = (s * kNT + tid) * 8;
         float x[8];
-        unpack8<DT>(lw, x);
+        float mx = kLowest;
+        if (in_range) {
+            const int v0 = (s * kNT + tid) * 8;
+            unpack8<DT>(lw, x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
+            for (int e = 0; e < 8; ++e) {
+                if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
+                mx = fmaxf(mx, x[e]);
+            }
+        }
+        if (!sampled) return;                                   // greedy: the arg-max is all the walk needs
+        const float gm = row16_max(mx);
+        float acc = 0.f;
+        if (in_range) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f((x[e] - gm) * cexp);
+        }
+        acc = row16_sum(acc);
+        if ((lane & 15) == 0) { part[s][wv * 4 + (lane >> 4)] = acc; gmax[s][wv * 4 + (lane >> 4)] = gm; }
     });
     best = wave_argmax(best);
     if (lane == 0) { wmax[wv] = best.v; warg[wv] = best.i; }
@@ -136,23 +156,22 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     for (int w = 1; w < kNW; ++w) best = argmax_merge(best, ArgMax{wmax[w], warg[w]});
     if (best.i >= V) best.i = 0;
     TreeNodeStat *st = stats + r;
-    if (T == 0.0f) {                                            // greedy: the arg-max is all the walk needs
+    if (!sampled) {
         if (tid == 0) { st->m = best.v; st->arg = best.i; st->Z = 1.0; }
         return;
     }
-    const float m = best.v, cexp = 1.4426950408889634f / T;
-    for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
-        float acc = 0.f;
-        if (in_range) {
-            float x[8];
-            unpack8<DT>(lw, x);
+    const float m = best.v;
+    // wavefront s puts the 64 group sums of step s on the row's maximum and adds them up
+    {
+        double t = 0.0;
+        if (wv < nsteps) t = (double)(part[wv][lane] * __builtin_amdgcn_exp2f((gmax[wv][lane] - m) * cexp));
+        t = wave_sum(t);
+        if (lane == 0) S[wv] = t;
+    }
+    __syncthreads();
+    double Z = 0.0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f((x[e] - m) * cexp);
-        }
-        acc = row16_sum(acc);
-        if ((lane & 15) == 0) part[s][wv * 4 + (lane >> 4)] = acc;
-    });
-    const double Z = finish_sweep(part, S, nsteps, wv, lane);
+    for (int s = 0; s < kNSteps; ++s) Z += S[s];
     if (tid == 0) { st->m = m; st->arg = best.i; st->Z = Z; }
     if (tid < kNSteps) st->S0[tid] = tid < nsteps ? S[tid] : 0.0;
 }
