@@ -266,3 +266,107 @@ def test_kv_compact_path_matches_oracle_bitwise(dtype, d, pkg):
     nt = np.int32 if dtype == "f32" else np.int16
     assert np.array_equal(dev.k_pages.view(it).cpu().numpy(), k2.view(nt))
     assert np.array_equal(dev.v_pages.view(it).cpu().numpy(), v2.view(nt))
+
+
+# ------------------------------------------------------------------ robustness
+def test_tree_step_replayed_from_a_hip_graph(pkg):
+    """The tree calls launch kernels only, so a captured tree step replays bit for bit with new inputs."""
+    import torch
+    steps = []
+    for s in range(3):
+        st = W.make_custom_step(700 + s, ctx_lens=[300, 77, 2500, 40, 1200, 640], spec_lens=[3, 0, 5, 2, 4, 1],
+                                n_q_heads=16, n_kv_heads=4, head_dim=128, dtype="bf16", vocab=8192,
+                                logits_dtype="bf16", temperature=[0.8, 1.0, 0.0, 0.7, 1.0, 0.9], poison=False,
+                                noise_sigma=0.5)
+        steps.append(W.attach_tree(st, max_width=2, seed=50 + s))
+    devs = [to_device(st) for st in steps]
+    kmax = steps[0].max_spec_len
+    buf = to_device(steps[0])
+    names = ("q", "k_pages", "v_pages", "block_table", "target_logits", "draft_probs", "draft_tokens", "uniforms",
+             "parents")
+    out = torch.empty_like(buf.q)
+    B = steps[0].batch
+    toks = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
+    path = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
+    alen = torch.empty((B,), dtype=torch.int32, device="cuda:0")
+    ws_a = torch.empty(32 << 20, dtype=torch.uint8, device="cuda:0")
+    ws_b = torch.empty(4 << 20, dtype=torch.uint8, device="cuda:0")
+
+    def run(d, o, t, a, p):
+        pkg.verify_attn(d.q, d.k_pages, d.v_pages, d.block_table, d.ctx_lens, d.spec_lens, o, max_spec_len=kmax,
+                        workspace=ws_a, parents=d.parents)
+        pkg.accept_tree(d.target_logits, d.draft_probs, d.draft_tokens, d.parents, d.uniforms, d.spec_lens,
+                        d.temperature, max_spec_len=kmax, out_tokens=t, out_accept_len=a, out_path=p, workspace=ws_b)
+
+    run(buf, out, toks, alen, path)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    _say("capturing tree attention + tree acceptance into a HIP graph")
+    with torch.cuda.graph(g):
+        run(buf, out, toks, alen, path)
+    for rep in range(2):
+        for s, d in enumerate(devs):
+            ref = (torch.empty_like(out), torch.empty_like(toks), torch.empty_like(alen), torch.empty_like(path))
+            run(d, *ref)
+            torch.cuda.synchronize()
+            for n in names:
+                getattr(buf, n).copy_(getattr(d, n))
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), ref[0].view(torch.int16)), (rep, s)
+            assert torch.equal(toks, ref[1]) and torch.equal(alen, ref[2]) and torch.equal(path, ref[3]), (rep, s)
+
+
+@pytest.mark.parametrize("kpath", ["fast", "vector"])
+def test_tree_accept_many_requests(kpath, oracle_mod, pkg):
+    """More requests than a plan workgroup has threads (the metadata scan loops) and than the device has
+    compute units (several walk workgroups per unit)."""
+    rng = np.random.default_rng(12)
+    B = 1500
+    spec = rng.integers(0, 6, size=B).astype(np.int32)
+    st = W.make_custom_step(55, ctx_lens=spec + 1, spec_lens=spec, vocab=512, logits_dtype="bf16",
+                            temperature=rng.choice([0.0, 0.9], size=B), attention=False, noise_sigma=0.4,
+                            name="tree-many")
+    W.attach_tree(st, max_width=3)
+    _check_tree_accept(st, oracle_mod, pkg, kpath=kpath)
+
+
+def test_malformed_parents_are_forced_into_the_request(oracle_mod, pkg):
+    """Parent indices outside [0, j) for node j are clamped into that range (a root keeps no parent):
+    the outputs are those of the clamped tree, and nothing is read or written outside the request."""
+    import torch
+    st = W.make_custom_step(77, ctx_lens=[40, 300, 33, 700], spec_lens=[5, 9, 0, 12], n_q_heads=8, n_kv_heads=2,
+                            head_dim=128, dtype="bf16", vocab=2048, logits_dtype="bf16", noise_sigma=0.4,
+                            name="tree-malformed")
+    W.attach_tree(st, max_width=3)
+    good = st.parents.copy()
+    bad = good.copy()
+    cu = st.cu_q
+    rng = np.random.default_rng(3)
+    for i in range(st.batch):
+        n = int(st.spec_lens[i]) + 1
+        bad[cu[i]] = int(rng.integers(-5, 100))                      # the root's entry is ignored
+        for j in range(1, n):
+            r = rng.random()
+            if r < 0.25:
+                bad[cu[i] + j] = j + int(rng.integers(0, 1000))      # too large -> j - 1
+                good[cu[i] + j] = j - 1
+            elif r < 0.5:
+                bad[cu[i] + j] = -int(rng.integers(1, 1000))         # negative -> 0
+                good[cu[i] + j] = 0
+    dev = to_device(st)
+    bad_dev = torch.from_numpy(bad).cuda()
+    kw = dict(max_spec_len=st.max_spec_len)
+    out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                          out_dtype=F32, parents=bad_dev, **kw)
+    res = {p: pkg.accept_tree(dev.target_logits, dev.draft_probs, dev.draft_tokens, bad_dev, dev.uniforms,
+                              dev.spec_lens, dev.temperature, path=p, **kw) for p in ("fast", "vector")}
+    torch.cuda.synchronize()
+    st.parents = good
+    ref, _ = oracle_mod.verify_attn_tree(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                                         good, dtype=st.dtype, want_rounded=False)
+    rep = compare_attention(out, ref, None, st.dtype)
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+    for p, (toks, alen, path) in res.items():
+        arep = compare_accept_tree(st, toks.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), oracle_mod)
+        assert arep["hard_mismatches"] == 0, (p, arep["details"][:3])
