@@ -23,12 +23,10 @@
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"
+#include "row_stream.h"
 
 namespace adaspec {
 
-constexpr int kNT = 1024;
-constexpr int kNW = kNT / kWave;
-constexpr int kNSteps = 16;             // V <= kNT * 8 * kNSteps
 constexpr int kHoist = 3;               // stages whose 1/R is kept in registers during a sweep
 
 __device__ __forceinline__ int sane_parent_f(int p, int j) { return j == 0 ? -1 : min(max(p, 0), j - 1); }
@@ -36,71 +34,11 @@ __device__ __forceinline__ int sane_parent_f(int p, int j) { return j == 0 ? -1 
 // what kernel 1 leaves per node
 struct TreeNodeStat {
     float  m;               // maximum logit
-    int    arg;             // its lowest index
+    int    arg;             // its lowest index (greedy requests; 0 for sampled ones, which never emit it)
     double Z;               // sum_v 2^((l_v - m) c) = sum of S0[]      (sampled requests only)
     double S0[kNSteps];     // the same sum step by step
 };
 size_t tree_node_stat_bytes() { return sizeof(TreeNodeStat); }
-
-template <class DT>
-__device__ __forceinline__ void unpack8(const uint4 &w, float (&x)[8])
-{
-    x[0] = Pair16<DT>::lo(w.x); x[1] = Pair16<DT>::hi(w.x);
-    x[2] = Pair16<DT>::lo(w.y); x[3] = Pair16<DT>::hi(w.y);
-    x[4] = Pair16<DT>::lo(w.z); x[5] = Pair16<DT>::hi(w.z);
-    x[6] = Pair16<DT>::lo(w.w); x[7] = Pair16<DT>::hi(w.w);
-}
-template <class DT>
-__device__ __forceinline__ float elem16(const char *row, int v)
-{
-    return Pair16<DT>::lo((uint32_t) reinterpret_cast<const uint16_t *>(row)[v]);
-}
-
-// Per-step totals from the 64 partial sums each step left in `part`: wavefront s adds up step s.
-// Every thread returns R = sum of S[]; ends on a barrier.
-__device__ __forceinline__ double finish_sweep(const float (&part)[kNSteps][kWave], double (&S)[kNSteps],
-                                               int nsteps, int wv, int lane)
-{
-    __syncthreads();
-    {
-        const double t = wave_sum(wv < nsteps ? (double)part[wv][lane] : 0.0);
-        if (lane == 0) S[wv] = t;
-    }
-    __syncthreads();
-    double R = 0.0;
-#pragma unroll
-    for (int s = 0; s < kNSteps; ++s) R += S[s];
-    return R;
-}
-
-// Walks the steps of a row with the loads of the next kDepth steps in flight: f(step, in_range, logits
-// word, draft-probability word).  A wavefront that waited for every step's data before asking for the next
-// would pay one memory round trip per step.
-constexpr int kDepth = 4;
-template <bool kWithProbs, class F>
-__device__ __forceinline__ void for_each_step(const char *lrow, const char *prow, int nsteps, int V, int tid, F f)
-{
-    uint4 lw[kDepth], qw[kDepth];
-    auto issue = [&](int j, int s) {
-        const int v0 = (s * kNT + tid) * 8;
-        if (s < nsteps && v0 < V) {
-            lw[j] = *reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2);
-            if (kWithProbs) qw[j] = *reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2);
-        }
-    };
-#pragma unroll
-    for (int j = 0; j < kDepth; ++j) { lw[j] = make_uint4(0, 0, 0, 0); qw[j] = make_uint4(0, 0, 0, 0); issue(j, j); }
-    for (int s0 = 0; s0 < nsteps; s0 += kDepth) {
-#pragma unroll
-        for (int j = 0; j < kDepth; ++j) {
-            const int s = s0 + j;
-            if (s < nsteps) {
-                f(s, (s * kNT + tid) * 8 < V, lw[j], qw[j]);
-                issue(j, s + kDepth);
-            }
-        }
-    }
-}
 
 // ---- kernel 1: statistics of every node ---------------------------------------------------------
 // ONE read of the row.  The sums of a step are taken relative to the maximum of the 128 elements of
@@ -125,42 +63,56 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     const float cexp = sampled ? 1.4426950408889634f / T : 0.f;
     constexpr float kLowest = -3.0e38f;                          // stands in for -inf: differences stay defined
 
-    ArgMax best{-INFINITY, V};
+    TreeNodeStat *st = stats + r;
+    if (!sampled) {
+        // greedy: the arg-max (lowest index on ties) is all the walk needs
+        ArgMax best{-INFINITY, V};
+        for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
+            if (!in_range) return;
+            const int v0 = (s * kNT + tid) * 8;
+            float x[8];
+            unpack8<DT>(lw, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
+        });
+        best = wave_argmax(best);
+        if (lane == 0) { wmax[wv] = best.v; warg[wv] = best.i; }
+        __syncthreads();
+        best = ArgMax{wmax[0], warg[0]};
+#pragma unroll
+        for (int w = 1; w < kNW; ++w) best = argmax_merge(best, ArgMax{wmax[w], warg[w]});
+        if (best.i >= V) best.i = 0;
+        if (tid == 0) { st->m = best.v; st->arg = best.i; st->Z = 1.0; }
+        return;
+    }
+    // sampled: maximum and normaliser; the index of the maximum is not needed (a sampled walk never emits it)
+    float tmax = kLowest;
     for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
         float x[8];
         float mx = kLowest;
         if (in_range) {
-            const int v0 = (s * kNT + tid) * 8;
             unpack8<DT>(lw, x);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if (x[e] > best.v) best = ArgMax{x[e], v0 + e};
-                mx = fmaxf(mx, x[e]);
-            }
+            for (int e = 0; e < 8; ++e) mx = fmaxf(mx, x[e]);
         }
-        if (!sampled) return;                                   // greedy: the arg-max is all the walk needs
         const float gm = row16_max(mx);
+        tmax = fmaxf(tmax, gm);
         float acc = 0.f;
         if (in_range) {
+            const float off = fminf(-gm * cexp, 3.0e38f);        // stays finite when the whole group is -inf
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f((x[e] - gm) * cexp);
+            for (int e = 0; e < 8; ++e) acc += __builtin_amdgcn_exp2f(fmaf(x[e], cexp, off));
         }
         acc = row16_sum(acc);
         if ((lane & 15) == 0) { part[s][wv * 4 + (lane >> 4)] = acc; gmax[s][wv * 4 + (lane >> 4)] = gm; }
     });
-    best = wave_argmax(best);
-    if (lane == 0) { wmax[wv] = best.v; warg[wv] = best.i; }
+    tmax = wave_max(tmax);
+    if (lane == 0) wmax[wv] = tmax;
     __syncthreads();
-    best = ArgMax{wmax[0], warg[0]};
+    float m = wmax[0];
 #pragma unroll
-    for (int w = 1; w < kNW; ++w) best = argmax_merge(best, ArgMax{wmax[w], warg[w]});
-    if (best.i >= V) best.i = 0;
-    TreeNodeStat *st = stats + r;
-    if (!sampled) {
-        if (tid == 0) { st->m = best.v; st->arg = best.i; st->Z = 1.0; }
-        return;
-    }
-    const float m = best.v;
+    for (int w = 1; w < kNW; ++w) m = fmaxf(m, wmax[w]);
     // wavefront s puts the 64 group sums of step s on the row's maximum and adds them up
     {
         double t = 0.0;
@@ -172,7 +124,7 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     double Z = 0.0;
 #pragma unroll
     for (int s = 0; s < kNSteps; ++s) Z += S[s];
-    if (tid == 0) { st->m = m; st->arg = best.i; st->Z = Z; }
+    if (tid == 0) { st->m = m; st->arg = 0; st->Z = Z; }
     if (tid < kNSteps) st->S0[tid] = tid < nsteps ? S[tid] : 0.0;
 }
 
@@ -252,17 +204,48 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
         }
         return acc;
     };
+    // The common stages written out: stage 1..kHoist, no stage before it kept its distribution, and this
+    // one does not either.  Then r = max(0, .. max(0, max(0, p - q) / R_1 - q) / R_2 .. - q) is straight-line
+    // code: the same float operations as dist() performs, without its per-stage selects.
+    auto mass8_plain = [&](auto stage_tag, bool in_range, const uint4 &lw, const uint4 &qw,
+                           const float (&inv)[kHoist]) -> float {
+        constexpr int kStage = decltype(stage_tag)::value;
+        float acc = 0.f;
+        if (in_range) {
+            float x[8], q[8];
+            unpack8<DT>(lw, x);
+            unpack8<DT>(qw, q);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float P = __builtin_amdgcn_exp2f((x[e] - m) * cexp) * invZ;
+#pragma unroll
+                for (int j = 1; j < kStage; ++j) P = fmaxf(0.f, P - q[e]) * inv[j - 1];
+                acc += fmaxf(0.f, P - q[e]);
+            }
+        }
+        return acc;
+    };
     // one sweep at stage >= 1 (both rows)
     auto sweep = [&](int s_stage, bool keep_last) -> double {
         float inv[kHoist];
 #pragma unroll
         for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < s_stage) ? sm.inv_r[j + 1] : 1.0f;
         const unsigned long long kept = sm.kept;
-        for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
-            float rv[8];
-            const float acc = row16_sum(mass8(in_range, lw, qw, s_stage, keep_last, inv, kept, rv));
-            if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
-        });
+        auto plain = [&](auto stage_tag) {
+            for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
+                const float acc = row16_sum(mass8_plain(stage_tag, in_range, lw, qw, inv));
+                if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
+            });
+        };
+        if (!keep_last && kept == 0ull && s_stage == 1) plain(std::integral_constant<int, 1>{});
+        else if (!keep_last && kept == 0ull && s_stage == 2) plain(std::integral_constant<int, 2>{});
+        else if (!keep_last && kept == 0ull && s_stage == 3) plain(std::integral_constant<int, 3>{});
+        else
+            for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
+                float rv[8];
+                const float acc = row16_sum(mass8(in_range, lw, qw, s_stage, keep_last, inv, kept, rv));
+                if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
+            });
         return finish_sweep(sm.part, sm.S, nsteps, wv, lane);
     };
 
