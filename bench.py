@@ -300,7 +300,7 @@ def main() -> int:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"{args.workload}:{args.path}")
+        traffic = json.load(open(tpath)).get(f"{args.workload}{'-tree%d' % args.tree if tree else ''}:{args.path}")
     rec = {
         "metric": "verified query-tokens/sec per verify step (attn+accept); achieved HBM GB/s",
         "value": st.total_q / (ms_step * 1e-3),
