@@ -47,18 +47,65 @@ size_t tree_node_stat_bytes() { return sizeof(TreeNodeStat); }
 // per element, as a second sweep would, but the row is not fetched a second time.
 template <class DT>
 __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
-    const char *__restrict__ logits, const float *__restrict__ temperature,
-    const int32_t *__restrict__ row_req, int B, int V, int64_t lstride, TreeNodeStat *__restrict__ stats)
+    const char *__restrict__ logits, const int32_t *__restrict__ spec_lens,
+    const float *__restrict__ temperature, int B, int V, int max_spec_len, int64_t lstride,
+    TreeNodeStat *__restrict__ stats)
 {
     __shared__ float wmax[kNW];
     __shared__ int warg[kNW];
     __shared__ float part[kNSteps][kWave], gmax[kNSteps][kWave];
     __shared__ double S[kNSteps];
+    __shared__ int wtot[kNW], owner;
+    __shared__ float owner_T;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r = blockIdx.x;
-    const float T = temperature[min(max(row_req[r], 0), B - 1)];
     const char *lrow = logits + (int64_t)r * lstride * 2;
     const int nsteps = ceil_div(V / 8, kNT);
+
+    // The first 1024 draft lengths and temperatures, then the first steps of the row: all requested before
+    // anything is waited for.  Which request owns row r (only its temperature is needed) is found by a block
+    // scan of n_i = k_i + 1, 1024 requests at a time, while the row's data travels.
+    int n_first = 0;
+    float t_first = 0.f;
+    if (tid < B) {
+        n_first = min(max(spec_lens[tid], 0), max_spec_len) + 1;
+        t_first = temperature[tid];
+    }
+    RowPipe<false> pipe;
+    pipe.start(lrow, lrow, nsteps, V, tid);
+    if (tid == 0) owner = -1;
+    {
+        int carry = 0;
+        for (int base = 0; base < B; base += kNT) {
+            const int i = base + tid;
+            int n = n_first;
+            float tt = t_first;
+            if (base > 0) {
+                n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+                tt = i < B ? temperature[i] : 0.f;
+            }
+            const int inc = wave_scan_incl_dpp(n);
+            lds_barrier();                                      // (later trips: wtot of the trip before has been read)
+            if (lane == 63) wtot[wv] = inc;
+            lds_barrier();                                      // LDS only: the row's loads stay in flight
+            int pre = carry, tot = carry;
+#pragma unroll
+            for (int w = 0; w < kNW; ++w) {
+                if (w < wv) pre += wtot[w];
+                tot += wtot[w];
+            }
+            const int start = pre + inc - n;
+            if (i < B && r >= start && r < start + n) { owner = i; owner_T = tt; }
+            carry = tot;
+            if (r < carry) break;                               // uniform: found
+        }
+    }
+    lds_barrier();
+    if (owner < 0) {                                            // no request owns this row (inconsistent metadata)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+    const float T = owner_T;
     const bool sampled = T != 0.0f;
     const float cexp = sampled ? 1.4426950408889634f / T : 0.f;
     constexpr float kLowest = -3.0e38f;                          // stands in for -inf: differences stay defined
@@ -67,7 +114,7 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     if (!sampled) {
         // greedy: the arg-max (lowest index on ties) is all the walk needs
         ArgMax best{-INFINITY, V};
-        for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
+        pipe.run([&](int s, bool in_range, const uint4 &lw, const uint4 &) {
             if (!in_range) return;
             const int v0 = (s * kNT + tid) * 8;
             float x[8];
@@ -88,7 +135,7 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     }
     // sampled: maximum and normaliser; the index of the maximum is not needed (a sampled walk never emits it)
     float tmax = kLowest;
-    for_each_step<false>(lrow, lrow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &) {
+    pipe.run([&](int s, bool in_range, const uint4 &lw, const uint4 &) {
         float x[8];
         float mx = kLowest;
         if (in_range) {
@@ -139,6 +186,7 @@ struct WalkScratch {
     unsigned long long kept;            // bit s: stage s kept P_{s-1} (no positive part)
     unsigned long long kids;
     int fallback, hit, last_thread;
+    int fallback_tot[kNW];              // (start-up only) per-wavefront row counts of the requests before this one
 };
 
 template <class DT>
@@ -146,7 +194,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ parents,
     const float *__restrict__ uniforms, const int32_t *__restrict__ spec_lens,
-    const float *__restrict__ temperature, const int32_t *__restrict__ cu_q,
+    const float *__restrict__ temperature,
     const TreeNodeStat *__restrict__ stats, int V, int total_q, int max_spec_len, int64_t lstride,
     int64_t pstride, int out_stride, int32_t *__restrict__ out_tokens,
     int32_t *__restrict__ out_accept_len, int32_t *__restrict__ out_path)
@@ -154,10 +202,21 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     __shared__ WalkScratch sm;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int i = blockIdx.x;
-    const int r0 = cu_q[i];
     const int k = min(max(spec_lens[i], 0), max_spec_len);
-    if (r0 < 0 || r0 + k + 1 > total_q) return;                 // inconsistent metadata: leave the request alone
     const float T = temperature[i];
+    // first row of the request: the rows of the requests before it, added up by the workgroup
+    int r0;
+    {
+        int part = 0;
+        for (int j = tid; j < i; j += kNT) part += min(max(spec_lens[j], 0), max_spec_len) + 1;
+        part = wave_sum(part);
+        if (lane == 0) sm.fallback_tot[wv] = part;
+        __syncthreads();
+        r0 = 0;
+#pragma unroll
+        for (int w = 0; w < kNW; ++w) r0 += sm.fallback_tot[w];
+    }
+    if (r0 + k + 1 > total_q) return;                           // inconsistent metadata: leave the request alone
     const float cexp = T == 0.0f ? 0.f : 1.4426950408889634f / T;
     const int nsteps = ceil_div(V / 8, kNT);
     int32_t *o = out_tokens + (int64_t)i * out_stride;
@@ -397,11 +456,11 @@ hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, 
     auto launch = [&](auto tag) {
         using DT = decltype(tag);
         hipLaunchKernelGGL((tree_node_stats_kernel<DT>), dim3(d.total_q), dim3(kNT), 0, a.stream,
-                           (const char *)a.logits, a.temperature, (const int32_t *)(a.ws + a.plan.off_row_req),
-                           d.batch, d.vocab, d.logits_row_stride, stats);
+                           (const char *)a.logits, a.spec_lens, a.temperature, d.batch, d.vocab, d.max_spec_len,
+                           d.logits_row_stride, stats);
         hipLaunchKernelGGL((accept_tree_walk_fast_kernel<DT>), dim3(d.batch), dim3(kNT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, parents, a.uniforms,
-                           a.spec_lens, a.temperature, (const int32_t *)(a.ws + a.plan.off_cu_q), stats, d.vocab,
+                           a.spec_lens, a.temperature, stats, d.vocab,
                            d.total_q, d.max_spec_len, d.logits_row_stride, d.probs_row_stride, d.out_stride,
                            a.out_tokens, a.out_accept_len, out_path);
     };
