@@ -438,6 +438,53 @@ def main() -> int:
         "kv_append_ms": t_append, "commit_ms": t_commit,
         "note": "not part of `value`; draft_sample is the kernel between library-recorded events, kv_append and "
                 "commit are whole calls issued back to back (host launch overhead dominates them)"}
+    # the same step over draft TREES (not part of `value`): every request's drafts rewired into a tree of up
+    # to 3 children per node, tree attention + tree acceptance, same cold-cache rotation of the big tensors
+    import copy
+    st_t = copy.copy(st)
+    st_t.draft_tokens = st.draft_tokens.copy()
+    st_t.notes = dict(st.notes)
+    W.attach_tree(st_t, max_width=3)
+    t_par = torch.from_numpy(st_t.parents).to("cuda:0")
+    t_tok = torch.from_numpy(st_t.draft_tokens).to("cuda:0")
+    t_path = torch.empty((B, kmax + 1), dtype=torch.int32, device="cuda:0")
+
+    def tree_step(k):
+        dv = devs[k % ncopies]
+        pkg.verify_attn(dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.ctx_lens, dv.spec_lens, out,
+                        max_spec_len=kmax, path=attn_path, workspace=ws_attn, parents=t_par, stream=stream)
+        pkg.accept_tree(dv.target_logits, dv.draft_probs, t_tok, t_par, dv.uniforms, dv.spec_lens, dv.temperature,
+                        max_spec_len=kmax, out_tokens=toks, out_accept_len=alen, out_path=t_path,
+                        workspace=ws_acc, stream=stream)
+
+    n_tree = 60
+    ev_t = HipEvents(n_tree // 4)
+    with torch.cuda.stream(stream):
+        for k in range(6):
+            tree_step(k)
+        torch.cuda.synchronize()
+        tt0 = time.perf_counter()
+        for k in range(n_tree):
+            if k % 4 == 0:
+                pkg.set_timing_events(1, ev_t.start[k // 4], ev_t.stop[k // 4])
+            else:
+                pkg.set_timing_events(1, None, None)
+            tree_step(k)
+        torch.cuda.synchronize()
+        ms_tree = (time.perf_counter() - tt0) * 1e3 / n_tree
+    pkg.set_timing_events(1, None, None)
+    acc_tree_ms = sum(ev_t.elapsed_ms(k) for k in range(n_tree // 4)) / (n_tree // 4)
+    ev_t.close()
+    walk = W.tree_accept_bytes_walk_form(st_t, t_path.cpu().numpy(), alen.cpu().numpy())
+    rec["tree_step"] = {
+        "workload": st.name + "-tree3", "ms_per_step": ms_tree, "value": st.total_q / (ms_tree * 1e-3),
+        "unit": "verified tree nodes/s", "nodes_with_children": int(W.tree_internal_nodes(st_t).sum()),
+        "mean_accepted_nodes": float(alen.float().mean().item()),
+        "accept_kernels_ms": acc_tree_ms, "accept_algorithmic_bytes": walk["accept"],
+        "accept_frac": gbs(walk["accept"], acc_tree_ms) / HBM_PEAK_GBS,
+        "note": "not part of `value`; tree attention (ancestor masks) + tree acceptance (node statistics, then one "
+                "workgroup per request walks its tree); bytes of the walk form (rows the walk skips not counted); "
+                "`bench.py --tree 3` gives the full record for this workload"}
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(st)
         rec["cpu_baseline"]["gpu_over_oracle"] = rec["value"] / rec["cpu_baseline"]["value"]
