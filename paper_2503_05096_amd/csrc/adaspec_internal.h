@@ -145,6 +145,7 @@ hipError_t launch_accept_tree_nodes(const AcceptArgs &a, const int32_t *parents)
 // 16-bit rows (shapes of the register-resident chain kernel): node statistics, then one workgroup per request
 // walks its tree and writes the outputs (no separate walk kernel)
 size_t tree_node_stat_bytes();
+bool tree_fast_needs_plan(const adaspec_accept_dims &d);   // large batches: row offsets from launch_accept_plan
 hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, int32_t *out_path);
 hipError_t launch_accept_tree_walk(const AcceptArgs &a, int32_t *out_path);
 hipError_t launch_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_table,

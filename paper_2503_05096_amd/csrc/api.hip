@@ -327,8 +327,8 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
     a.out_tokens = out_tokens; a.out_accept_len = out_accept_len;
     a.dims = *dims; a.ws = static_cast<char *>(workspace);
     a.stream = static_cast<hipStream_t>(stream);
-    // (the fast kernels find their rows and requests themselves; only the portable ones need the plan)
-    if (!fast && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
+    // (the fast kernels find their rows and requests themselves, up to a few thousand requests)
+    if ((!fast || tree_fast_needs_plan(*dims)) && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
     if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
         return ADASPEC_ERR_HIP;
     if (fast) {

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     const char *__restrict__ logits, const char *__restrict__ probs,
     const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ parents,
     const float *__restrict__ uniforms, const int32_t *__restrict__ spec_lens,
-    const float *__restrict__ temperature,
+    const float *__restrict__ temperature, const int32_t *__restrict__ cu_q,
     const TreeNodeStat *__restrict__ stats, int V, int total_q, int max_spec_len, int64_t lstride,
     int64_t pstride, int out_stride, int32_t *__restrict__ out_tokens,
     int32_t *__restrict__ out_accept_len, int32_t *__restrict__ out_path)
@@ -204,9 +204,12 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     const int i = blockIdx.x;
     const int k = min(max(spec_lens[i], 0), max_spec_len);
     const float T = temperature[i];
-    // first row of the request: the rows of the requests before it, added up by the workgroup
+    // first row of the request: from the metadata kernel if the caller ran it (large batches), else the rows
+    // of the requests before it, added up by the workgroup
     int r0;
-    {
+    if (cu_q != nullptr) {
+        r0 = cu_q[i];
+    } else {
         int part = 0;
         for (int j = tid; j < i; j += kNT) part += min(max(spec_lens[j], 0), max_spec_len) + 1;
         part = wave_sum(part);
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
 #pragma unroll
         for (int w = 0; w < kNW; ++w) r0 += sm.fallback_tot[w];
     }
-    if (r0 + k + 1 > total_q) return;                           // inconsistent metadata: leave the request alone
+    if (r0 < 0 || r0 + k + 1 > total_q) return;                 // inconsistent metadata: leave the request alone
     const float cexp = T == 0.0f ? 0.f : 1.4426950408889634f / T;
     const int nsteps = ceil_div(V / 8, kNT);
     int32_t *o = out_tokens + (int64_t)i * out_stride;
@@ -448,6 +451,10 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     }
 }
 
+// Every walk workgroup adds up the rows of the requests before its own: fine for a few thousand requests,
+// quadratic beyond; larger batches take the row offsets from the metadata kernel.
+bool tree_fast_needs_plan(const adaspec_accept_dims &d) { return d.batch > 2048; }
+
 hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, int32_t *out_path)
 {
     const adaspec_accept_dims &d = a.dims;
@@ -460,7 +467,8 @@ hipError_t launch_accept_tree_fast(const AcceptArgs &a, const int32_t *parents, 
                            d.logits_row_stride, stats);
         hipLaunchKernelGGL((accept_tree_walk_fast_kernel<DT>), dim3(d.batch), dim3(kNT), 0, a.stream,
                            (const char *)a.logits, (const char *)a.probs, a.draft_tokens, parents, a.uniforms,
-                           a.spec_lens, a.temperature, stats, d.vocab,
+                           a.spec_lens, a.temperature,
+                           tree_fast_needs_plan(d) ? (const int32_t *)(a.ws + a.plan.off_cu_q) : nullptr, stats, d.vocab,
                            d.total_q, d.max_spec_len, d.logits_row_stride, d.probs_row_stride, d.out_stride,
                            a.out_tokens, a.out_accept_len, out_path);
     };
