@@ -308,6 +308,16 @@ int adaspec_verify_attn_tree(const void *q, const void *k_pages, const void *v_p
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * adaspec_check_tree_parents - optional device-side check of a parent array (the tree calls force
+ * malformed entries into range silently): enqueues one small kernel that writes 16 (bit 4) to
+ * *err_flags (device int32) if some node j >= 1 of some request names a parent outside [0, j), else 0.
+ * The root's entry is not looked at.  spec_lens and total_q must be consistent
+ * (adaspec_check_ragged_inputs).
+ */
+int adaspec_check_tree_parents(const int32_t *parents, const int32_t *spec_lens, int32_t batch,
+                               int32_t total_q, int32_t max_spec_len, int32_t *err_flags, void *stream);
+
+/*
  * adaspec_accept_tree - acceptance walk over the tree of every request.
  *   target_logits [TQ][V]  row of node j: the target's logits for the token after node j
  *   draft_probs   [TD][V]  request i owns rows cu_q[i]-i ..; row j (0 <= j < k_i) is the draft

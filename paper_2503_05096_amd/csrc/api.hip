@@ -377,6 +377,19 @@ int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_l
     return ADASPEC_OK;
 }
 
+int adaspec_check_tree_parents(const int32_t *parents, const int32_t *spec_lens, int32_t batch, int32_t total_q,
+                               int32_t max_spec_len, int32_t *err_flags, void *stream)
+{
+    if (batch < 0 || total_q < batch || max_spec_len < 0) return ADASPEC_ERR_DIM;
+    if ((int64_t)total_q > (int64_t)batch * (max_spec_len + 1)) return ADASPEC_ERR_DIM;
+    if (max_spec_len > 63) return ADASPEC_ERR_UNSUPPORTED;
+    if (!parents || !spec_lens || !err_flags) return ADASPEC_ERR_NULL;
+    if (launch_check_tree_parents(parents, spec_lens, batch, total_q, max_spec_len, err_flags,
+                                  static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
 int adaspec_kv_append(const void *k_new, const void *v_new, void *k_pages, void *v_pages,
                       const int32_t *block_table, const int32_t *ctx_lens,
                       const int32_t *spec_lens, const adaspec_attn_dims *d, void *stream)

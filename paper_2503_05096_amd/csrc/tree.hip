@@ -51,6 +51,51 @@ hipError_t launch_tree_masks(const AttnArgs &a)
     return hipGetLastError();
 }
 
+// Device-side check of a parent array (see adaspec.h): bit 4 of *err_flags is set if some node j >= 1 of some
+// request names a parent outside [0, j).  One thread per request; cu_q by a block scan, 256 requests at a time.
+__global__ __launch_bounds__(256) void check_tree_parents_kernel(
+    const int32_t *__restrict__ parents, const int32_t *__restrict__ spec_lens, int B, int total_q,
+    int max_spec_len, int32_t *__restrict__ err_flags)
+{
+    __shared__ int wtot[4];
+    __shared__ int bad;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid == 0) bad = 0;
+    int carry = 0, mine_bad = 0;
+    for (int base = 0; base < B; base += 256) {
+        const int i = base + tid;
+        const int n = i < B ? min(max(spec_lens[i], 0), max_spec_len) + 1 : 0;
+        const int inc = wave_scan_incl(n, lane);
+        __syncthreads();
+        if (lane == 63) wtot[wv] = inc;
+        __syncthreads();
+        int pre = carry, tot = carry;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wv) pre += wtot[w];
+            tot += wtot[w];
+        }
+        const int r0 = pre + inc - n;
+        if (i < B && r0 + n <= total_q)
+            for (int j = 1; j < n; ++j) {
+                const int p = parents[r0 + j];
+                if (p < 0 || p >= j) mine_bad = 1;
+            }
+        carry = tot;
+    }
+    if (mine_bad) atomicOr(&bad, 1);
+    __syncthreads();
+    if (tid == 0) *err_flags = bad ? 16 : 0;
+}
+
+hipError_t launch_check_tree_parents(const int32_t *parents, const int32_t *spec_lens, int B, int total_q,
+                                     int max_spec_len, int32_t *err_flags, hipStream_t stream)
+{
+    hipLaunchKernelGGL(check_tree_parents_kernel, dim3(1), dim3(256), 0, stream, parents, spec_lens, B, total_q,
+                       max_spec_len, err_flags);
+    return hipGetLastError();
+}
+
 // ---- acceptance of one node --------------------------------------------------------------
 // One workgroup of 256 threads per node (= logits row), any storage types, any vocabulary size.
 //

@@ -262,6 +262,10 @@ def test_tree_calls_validate_on_the_host():
     assert tree_acc(a, [PTR] * 10, ws=PTR + 64) == -4
     assert tree_acc(_accept_dims(batch=0, total_q=0, total_draft=0), [None] * 10, None, 0) == 0
 
+    chk = L.adaspec_check_tree_parents
+    assert chk(None, PTR, 2, 5, 3, PTR, None) == -1 and chk(PTR, PTR, 2, 5, 3, None, None) == -1
+    assert chk(PTR, PTR, 2, 9, 3, PTR, None) == -2 and chk(PTR, PTR, 2, 66, 64, PTR, None) == -6
+
     compact = lambda dims, ptrs, stride=4: L.adaspec_kv_compact_path(*ptrs, C.byref(dims), stride, None)
     for k in range(7):
         p = [PTR] * 7

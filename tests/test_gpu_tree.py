@@ -357,6 +357,9 @@ def test_malformed_parents_are_forced_into_the_request(oracle_mod, pkg):
     dev = to_device(st)
     bad_dev = torch.from_numpy(bad).cuda()
     kw = dict(max_spec_len=st.max_spec_len)
+    # the optional device-side check tells the two arrays apart (the root's entry is never looked at)
+    assert pkg.check_tree_parents(bad_dev, dev.spec_lens, **kw) == 16
+    assert pkg.check_tree_parents(torch.from_numpy(good).cuda(), dev.spec_lens, **kw) == 0
     out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
                           out_dtype=F32, parents=bad_dev, **kw)
     res = {p: pkg.accept_tree(dev.target_logits, dev.draft_probs, dev.draft_tokens, bad_dev, dev.uniforms,
