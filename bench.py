@@ -318,7 +318,12 @@ def main() -> int:
                              f"WARM: {ncopies} input cop{'y' if ncopies == 1 else 'ies'}, may be served from the memory-side cache")},
         "roofline": {"bound": "hbm", "kernel": "verify-attention main kernel",
                      "achieved": gbs(nbytes["attn"], attn_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs(nbytes["attn"], attn_ms) / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": gbs(nbytes["attn"], attn_ms) / HBM_PEAK_GBS,
+                     # HBM bytes of this kernel per launch (fetched + written), from the committed rocprofv3 --pmc
+                     # runs of this very command (profiles/), counters scaled by the plain-copy calibration
+                     "traffic": (None if traffic is None else
+                                 traffic["attention_main"]["fetch_bytes"] + traffic["attention_main"]["write_bytes"]),
+                     "traffic_detail": traffic,
                      "algorithmic_bytes": nbytes["attn"], "avg_kernel_ms": attn_ms,
                      "kernel_ms": spread(attn_all)},
         "roofline_accept": {"bound": "hbm",
