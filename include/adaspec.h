@@ -341,8 +341,9 @@ int adaspec_check_tree_parents(const int32_t *parents, const int32_t *spec_lens,
  * Dims and workspace as for adaspec_accept.  dims->path:
  *   VECTOR  the portable form (any storage types and vocabulary size): every node of every tree is
  *           evaluated, one workgroup per node, then a small kernel walks the results;
- *   FAST    same shapes as adaspec_accept's FAST: first the statistics of every node (two reads of its
- *           logits row, the second from the caches), then one workgroup per request walks its tree
+ *   FAST    16-bit logits/probs of one type, V % 8 == 0, V <= 524288, strides % 8 == 0, 16-byte aligned
+ *           base pointers: first the statistics of every node (one read of its logits row), then one
+ *           workgroup per request walks its tree
  *           and reads, at the nodes it reaches only, the logits and draft-probability rows once per
  *           rejected child;
  *   AUTO    FAST when it fits, else VECTOR.

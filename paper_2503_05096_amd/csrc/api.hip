@@ -310,7 +310,9 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
     if (dims->path != ADASPEC_PATH_AUTO && dims->path != ADASPEC_PATH_VECTOR && dims->path != ADASPEC_PATH_FAST)
         return ADASPEC_ERR_UNSUPPORTED;
     if (dims->max_spec_len > 63) return ADASPEC_ERR_UNSUPPORTED;
-    const bool fast_ok = accept_fast_path_supported(*dims, target_logits, draft_probs);
+    // (the fast tree kernels take the shapes of the streaming chain kernel: 16-bit rows of one type, V % 8 == 0,
+    // V <= 524288, strides % 8 == 0, 16-byte aligned)
+    const bool fast_ok = accept_stream_path_supported(*dims, target_logits, draft_probs);
     if (dims->path == ADASPEC_PATH_FAST && !fast_ok) return ADASPEC_ERR_UNSUPPORTED;
     const bool fast = fast_ok && dims->path != ADASPEC_PATH_VECTOR;
     if (dims->batch == 0) return ADASPEC_OK;

@@ -8,7 +8,7 @@ namespace adaspec {
 
 constexpr int kNT = 1024;
 constexpr int kNW = kNT / kWave;
-constexpr int kNSteps = 16;             // V <= kNT * 8 * kNSteps
+constexpr int kNSteps = 64;             // V <= kNT * 8 * kNSteps = 524288
 
 
 template <class DT>
@@ -25,20 +25,19 @@ __device__ __forceinline__ float elem16(const char *row, int v)
     return Pair16<DT>::lo((uint32_t) reinterpret_cast<const uint16_t *>(row)[v]);
 }
 
-// Per-step totals from the 64 partial sums each step left in `part`: wavefront s adds up step s.
-// Every thread returns R = sum of S[]; ends on a barrier.
+// Per-step totals from the 64 partial sums each step left in `part`: wavefront w adds up steps w, w + 16, ...
+// Every thread returns R = sum of S[0 .. nsteps); ends on a barrier.
 __device__ __forceinline__ double finish_sweep(const float (&part)[kNSteps][kWave], double (&S)[kNSteps],
                                                int nsteps, int wv, int lane)
 {
     __syncthreads();
-    {
-        const double t = wave_sum(wv < nsteps ? (double)part[wv][lane] : 0.0);
-        if (lane == 0) S[wv] = t;
+    for (int s = wv; s < nsteps; s += kNW) {
+        const double t = wave_sum((double)part[s][lane]);
+        if (lane == 0) S[s] = t;
     }
     __syncthreads();
     double R = 0.0;
-#pragma unroll
-    for (int s = 0; s < kNSteps; ++s) R += S[s];
+    for (int s = 0; s < nsteps; ++s) R += S[s];
     return R;
 }
 

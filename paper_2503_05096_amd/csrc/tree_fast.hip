@@ -1,5 +1,5 @@
 // Tree acceptance for 16-bit logits and draft probabilities of one type, V % 8 == 0,
-// V <= 131072 (the shapes of the register-resident chain kernel), in two kernels:
+// V <= 524288 (the shapes of the streaming chain kernel), in two kernels:
 //
 //   1. node statistics, one workgroup per node (= logits row), one read of the row: the maximum
 //      and its index, and for a sampled request the normaliser Z with its per-step parts S0[];
@@ -160,17 +160,14 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
     float m = wmax[0];
 #pragma unroll
     for (int w = 1; w < kNW; ++w) m = fmaxf(m, wmax[w]);
-    // wavefront s puts the 64 group sums of step s on the row's maximum and adds them up
-    {
-        double t = 0.0;
-        if (wv < nsteps) t = (double)(part[wv][lane] * __builtin_amdgcn_exp2f((gmax[wv][lane] - m) * cexp));
-        t = wave_sum(t);
-        if (lane == 0) S[wv] = t;
+    // wavefront w puts the 64 group sums of steps w, w + 16, ... on the row's maximum and adds them up
+    for (int s = wv; s < nsteps; s += kNW) {
+        const double t = wave_sum((double)(part[s][lane] * __builtin_amdgcn_exp2f((gmax[s][lane] - m) * cexp)));
+        if (lane == 0) S[s] = t;
     }
     __syncthreads();
     double Z = 0.0;
-#pragma unroll
-    for (int s = 0; s < kNSteps; ++s) Z += S[s];
+    for (int s = 0; s < nsteps; ++s) Z += S[s];
     if (tid == 0) { st->m = m; st->arg = 0; st->Z = Z; }
     if (tid < kNSteps) st->S0[tid] = tid < nsteps ? S[tid] : 0.0;
 }
@@ -381,8 +378,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
                 const double tau = (double)uniforms[2 * (int64_t)r + 1] * R;
                 int sstar = -1, last_pos_step = 0;
                 double before = 0.0, run = 0.0, before_last = 0.0;
-#pragma unroll
-                for (int s = 0; s < kNSteps; ++s) {
+                for (int s = 0; s < nsteps; ++s) {
                     const double Ss = sm.S[s];
                     if (Ss > 0.0) { last_pos_step = s; before_last = run; }
                     if (sstar < 0 && run + Ss > tau) { sstar = s; before = run; }

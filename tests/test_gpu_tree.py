@@ -139,12 +139,14 @@ def test_config_tree_accept_portable_kernel(cfg, width, oracle_mod, pkg):
 
 
 @pytest.mark.parametrize("dtype,V,sigma", [("bf16", 4096, 0.3), ("f16", 32000, 0.5), ("bf16", 131072, 0.6),
-                                           ("bf16", 8, 0.3)])
+                                           ("bf16", 8, 0.3), ("bf16", 200008, 0.6), ("f16", 524288, 0.8)])
 def test_tree_accept_fast_kernel_shapes(dtype, V, sigma, oracle_mod, pkg):
-    """The 1024-thread kernel on vocabularies from one partial step to the sixteen steps it holds, with a
-    draft close enough to the target that later children get tested and long paths occur."""
+    """The 1024-thread kernels on vocabularies from one partial step to the sixty-four steps they hold, with
+    a draft close enough to the target that later children get tested and long paths occur."""
     rng = np.random.default_rng(8)
     spec = np.array([0, 1, 8, 8, 20, 63, 3, 5, 12, 2, 7, 7, 30, 4], np.int32)
+    if V > 131072:
+        spec = spec[[0, 1, 2, 6, 7, 9]]                              # (keeps the host tensors of the big rows small)
     T = rng.choice([0.0, 0.6, 1.0, 1.4], size=spec.shape[0])
     st = W.make_custom_step(321, ctx_lens=spec + 1, spec_lens=spec, vocab=V, logits_dtype=dtype, temperature=T,
                             attention=False, noise_sigma=sigma, name=f"tree-fast-{dtype}-{V}")
@@ -152,7 +154,7 @@ def test_tree_accept_fast_kernel_shapes(dtype, V, sigma, oracle_mod, pkg):
     cu = st.cu_q
     st.parents[cu[2] + 1:cu[3]] = 0                                  # request 2: a star of 8 children
     rep, (toks, alen, path) = _check_tree_accept(st, oracle_mod, pkg, kpath="fast", max_near_tie_frac=0.2)
-    if V >= 4096:
+    if 4096 <= V <= 131072:
         assert alen.max().item() >= 2
 
 
