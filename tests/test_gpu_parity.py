@@ -495,3 +495,26 @@ def test_accept_with_padded_row_strides(path, oracle_mod, pkg):
     torch.cuda.synchronize()
     rep = compare_accept(st, toks.cpu().numpy(), alen.cpu().numpy(), oracle_mod)
     assert rep["hard_mismatches"] == 0 and rep["exact"] + rep["ratio_near_ties"] + rep["cdf_near_ties"] == st.batch, rep
+
+
+@pytest.mark.parametrize("path", ["vector", "fast", "stream", "two_pass"])
+def test_accept_with_masked_logits(path, oracle_mod, pkg):
+    """Logit masking (a share of every target row is -inf, the draft distribution 0 there): masked tokens are
+    never emitted, and every path still matches the oracle."""
+    rng = np.random.default_rng(31)
+    B = 40
+    spec = rng.integers(0, 7, size=B).astype(np.int32)
+    st = W.make_custom_step(640, ctx_lens=spec + 1, spec_lens=spec, vocab=8192, logits_dtype="bf16",
+                            temperature=rng.choice([0.0, 0.8, 1.0], size=B), attention=False, noise_sigma=0.7,
+                            masked_frac=0.35, name="masked-logits")
+    rep = check_accept(st, oracle_mod, pkg, path=path, max_near_tie_frac=0.1)
+    dev = to_device(st, attention=False)
+    toks, alen = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens,
+                            dev.temperature, max_spec_len=st.max_spec_len, path=path)
+    toks, alen = toks.cpu().numpy(), alen.cpu().numpy()
+    logits = W.to_f64(st.target_logits, st.logits_dtype)
+    cu = st.cu_q
+    for i in range(B):
+        for j in range(alen[i] + 1):
+            assert np.isfinite(logits[cu[i] + j, toks[i, j]]), (i, j)     # row j emitted token j
+    assert rep["hard_mismatches"] == 0

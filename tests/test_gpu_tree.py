@@ -402,3 +402,20 @@ def test_tree_accept_random_shapes(oracle_mod, pkg):
             rep, _ = _check_tree_accept(st, oracle_mod, pkg, kpath=kpath, max_near_tie_frac=1.0)
             near += rep["ratio_near_ties"] + rep["cdf_near_ties"]
     assert near <= 6, near                                           # rare by construction (1e-5 windows)
+
+
+@pytest.mark.parametrize("kpath", ["fast", "vector"])
+def test_tree_accept_with_masked_logits(kpath, oracle_mod, pkg):
+    """A share of every target row is -inf (and the draft distribution 0 there), whole 16-lane groups
+    included: the group-relative sums of the statistics kernel must not produce NaN."""
+    rng = np.random.default_rng(32)
+    B = 30
+    spec = rng.integers(0, 9, size=B).astype(np.int32)
+    st = W.make_custom_step(641, ctx_lens=spec + 1, spec_lens=spec, vocab=16384, logits_dtype="bf16",
+                            temperature=rng.choice([0.0, 0.8, 1.0], size=B), attention=False, noise_sigma=0.5,
+                            masked_frac=0.35, name="tree-masked-logits")
+    # mask a long aligned stretch of every row as well: whole steps without a finite logit
+    st.target_logits[:, 2048:12288] = np.uint16(0xFF80)
+    st.draft_probs[:, 2048:12288] = 0
+    W.attach_tree(st, max_width=3)
+    _check_tree_accept(st, oracle_mod, pkg, kpath=kpath, max_near_tie_frac=0.1)

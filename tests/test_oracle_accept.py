@@ -313,3 +313,21 @@ def test_rejects_bad_arguments(oracle_mod):
     with pytest.raises(ValueError):
         oracle_mod.accept(st.target_logits, st.draft_probs, st.draft_tokens, st.uniforms, st.spec_lens,
                           st.temperature, logits_dtype="f32", probs_dtype="f32", out_stride=2)
+
+
+def test_masked_tokens_are_never_emitted(oracle_mod):
+    """-inf target logits (masked tokens) have p = 0: never accepted unless q is 0 there too (then the ratio
+    test is skipped by the q == 0 rule only for tokens the draft can never propose), never recovered, never
+    drawn as bonus."""
+    rng = np.random.default_rng(5)
+    B = 200
+    spec = rng.integers(0, 5, size=B).astype(np.int32)
+    st = W.make_custom_step(88, ctx_lens=spec + 1, spec_lens=spec, vocab=32, attention=False, masked_frac=0.5,
+                            temperature=rng.choice([0.0, 0.6, 1.0], size=B), noise_sigma=0.5)
+    toks, alen, _ = oracle_mod.accept(st.target_logits, st.draft_probs, st.draft_tokens, st.uniforms, st.spec_lens,
+                                      st.temperature, logits_dtype="f32", probs_dtype="f32")
+    cu = st.cu_q
+    assert alen.max() >= 2
+    for i in range(B):
+        for j in range(alen[i] + 1):
+            assert np.isfinite(st.target_logits[cu[i] + j, toks[i, j]]), (i, j)

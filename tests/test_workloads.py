@@ -180,3 +180,18 @@ def test_tree_walk_form_bytes():
     # first children accepted all the way down to a leaf: no rejecting node
     path = np.array([[1, 3, -1, -1], [1, 2, 3, -1], [-1, -1, -1, -1]], np.int32)
     assert W.tree_accept_bytes_walk_form(st, path, np.array([2, 3, 0]))["rejecting_nodes_on_walks"] == 0
+
+
+def test_masked_logits_option():
+    st = W.make_custom_step(3, ctx_lens=[5, 9, 4], spec_lens=[3, 5, 0], vocab=64, logits_dtype="bf16",
+                            attention=False, masked_frac=0.4, temperature=[1.0, 0.7, 1.0])
+    logits = W.to_f64(st.target_logits, "bf16")
+    masked = np.isinf(logits)
+    assert 0.25 < masked.mean() < 0.55 and (logits[masked] < 0).all()
+    assert (~masked).any(axis=1).all()                                 # every row keeps a finite entry
+    q = W.to_f64(st.draft_probs, "bf16")
+    keep = np.ones(st.total_q, dtype=bool)
+    keep[st.cu_q[1:] - 1] = False
+    assert not np.isnan(q).any() and (q[masked[keep]] == 0).all()      # the draft puts no mass on masked tokens
+    for d in range(st.total_draft):
+        assert q[d, st.draft_tokens[d]] > 0

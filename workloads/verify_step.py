@@ -157,7 +157,7 @@ def _build(name: str, seed: int, ctx_lens, spec_lens, temperature, *,
            streams: Sequence[np.random.SeedSequence],
            attention: bool = True, acceptance: bool = True,
            poison: bool = True, pool_slack: float = 1.25,
-           sharp_key: bool = False, planted_ties: bool = False) -> VerifyStep:
+           sharp_key: bool = False, planted_ties: bool = False, masked_frac: float = 0.0) -> VerifyStep:
     (s_q, s_k, s_v, s_bt, s_logit, s_noise, s_tok, s_uni) = streams
     ctx_lens = np.asarray(ctx_lens, dtype=np.int32)
     spec_lens = np.asarray(spec_lens, dtype=np.int32)
@@ -219,6 +219,15 @@ def _build(name: str, seed: int, ctx_lens, spec_lens, temperature, *,
 
     if acceptance:
         st.target_logits = _normal(s_logit, (TQ, vocab), logits_sigma, logits_dtype)
+        if masked_frac > 0.0:
+            # logit masking as a serving stack applies it (banned tokens, grammar constraints): a random subset
+            # of every row is -inf in the target logits; the draft distribution built below is 0 there
+            g_m = np.random.Generator(np.random.PCG64(s_logit.spawn(2)[1]))
+            neg_inf = {"f32": np.float32(-np.inf), "f16": np.float16(-np.inf), "bf16": np.uint16(0xFF80)}[logits_dtype]
+            for r in range(TQ):
+                cols = g_m.random(vocab) < masked_frac
+                cols[int(g_m.integers(0, vocab))] = False              # at least one finite entry
+                st.target_logits[r][cols] = neg_inf
         if planted_ties:
             g_t = np.random.Generator(np.random.PCG64(s_logit.spawn(1)[0]))
             for r in range(TQ):
@@ -310,7 +319,7 @@ def _ragged(cfg: int, greedy: bool, s_ctx, s_spec, s_temp, batch: Optional[int])
 def make_verify_step(cfg: int, *, greedy: bool = False, batch: Optional[int] = None,
                      seed: Optional[int] = None, attention: bool = True,
                      acceptance: bool = True, poison: bool = True,
-                     sharp_key: bool = False, planted_ties: bool = False) -> VerifyStep:
+                     sharp_key: bool = False, planted_ties: bool = False, masked_frac: float = 0.0) -> VerifyStep:
     """One seeded draw of benchmark config `cfg` (1..5).  `greedy` selects the
     temperature-0 variant of config 4; `batch` shrinks the batch for quick tests."""
     seed = 5096000 + cfg if seed is None else seed
