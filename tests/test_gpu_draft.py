@@ -167,3 +167,17 @@ def test_draft_then_accept_roundtrip(oracle_mod, pkg):
     torch.cuda.synchronize()
     assert np.array_equal(alen.cpu().numpy(), spec)
     assert torch.all(conf_d > 0)
+
+
+@pytest.mark.parametrize("path", ["fast", "split", "vector"])
+def test_draft_sample_with_masked_logits(path, oracle_mod, pkg):
+    """A share of every draft-logits row is -inf (masked tokens), whole aligned stretches included: their
+    stored probability is exactly 0 and they are never drawn."""
+    st = W.make_custom_step(650, ctx_lens=[1] * 40, spec_lens=[0] * 40, vocab=40000, logits_dtype="bf16",
+                            attention=False, masked_frac=0.3)
+    logits = np.ascontiguousarray(st.target_logits)
+    logits[:, 8192:24576] = np.uint16(0xFF80)
+    rng = np.random.default_rng(9)
+    T = rng.choice(np.array([0.0, 0.7, 1.0], np.float32), 40).astype(np.float32)
+    u = rng.random(40).astype(np.float32)
+    _check(logits, "bf16", "bf16", T, u, oracle_mod, pkg, path=path)
