@@ -245,6 +245,7 @@ EDGE_SHAPES = [
     ([2100], [5], 64, 8, 128, "bf16"),                # one long request: many splits, 48 rows
     ([700, 90], [10, 7], 64, 8, 128, "f16"),          # 88 query rows per kv head: two row groups of 48
     ([4097, 4096, 4095], [0, 1, 2], 8, 1, 128, "bf16"),   # just around a split boundary, one kv head
+    ([65536, 40001], [2, 5], 8, 2, 128, "bf16"),      # very long contexts: up to 256 splits per request to combine
 ]
 
 
