@@ -116,7 +116,11 @@ typedef struct {
  *                               anything else in between.  Violations are undefined behaviour. */
 typedef enum { ADASPEC_PLAN_BUILD_AND_RUN = 0, ADASPEC_PLAN_BUILD_ONLY = 1, ADASPEC_PLAN_REUSE = 2 } adaspec_plan_mode;
 
-/* Device scratch needed by adaspec_verify_attn for these dims (0 on bad dims). */
+/* Device scratch needed by adaspec_verify_attn for these dims (0 on bad dims).
+ * Dims whose work does not fit the kernels' 32-bit counters are rejected with
+ * ADASPEC_ERR_UNSUPPORTED by every attention entry point: more than 2^24 (request, 256-token
+ * split) pairs at batch * ceil(max_pages_per_req * 16 / 256), or 2^31 or more
+ * (pair, kv head, row group) units. */
 size_t adaspec_verify_attn_workspace_bytes(const adaspec_attn_dims *dims);
 
 /*

@@ -75,6 +75,7 @@ struct AttnArgs {
 
 // Upper bound on W for which the workspace holds a schedule table.
 constexpr int kMaxSchedW = 1024;
+constexpr int64_t kMaxAttnItems = (int64_t)1 << 24;   // (request, split) work items of one attention call
 
 // Fills sched_w / n_row_groups / rows_per_group for the matrix-core kernel's launch of a.dims.
 void attn_mfma_shape(AttnArgs &a);

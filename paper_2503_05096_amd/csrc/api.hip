@@ -47,6 +47,14 @@ static int validate_attn_dims(const adaspec_attn_dims *d)
     if (!(d->scale >= 0.0f) || isinf(d->scale)) return ADASPEC_ERR_DIM;
     if (d->path == ADASPEC_PATH_FAST && !attn_fast_path_supported(*d)) return ADASPEC_ERR_UNSUPPORTED;
     if (d->plan_mode < ADASPEC_PLAN_BUILD_AND_RUN || d->plan_mode > ADASPEC_PLAN_REUSE) return ADASPEC_ERR_DIM;
+    {   // the kernels count work items and units in 32 bits: bound them at the shortest split (256 tokens)
+        const int64_t per_req = ((int64_t)d->max_pages_per_req * d->page_size + 255) / 256;
+        const int64_t items = (int64_t)d->batch * per_req;
+        const int64_t rows = (int64_t)(d->max_spec_len + 1) * (d->n_q_heads / d->n_kv_heads);
+        if (rows > (1 << 20) || items > kMaxAttnItems ||
+            items * d->n_kv_heads * attn_row_groups((int)rows) >= (int64_t)1 << 31)
+            return ADASPEC_ERR_UNSUPPORTED;
+    }
     return ADASPEC_OK;
 }
 

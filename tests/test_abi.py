@@ -59,6 +59,10 @@ def _call_accept(dims, ptrs=None, ws=PTR, ws_bytes=1 << 40):
     (dict(n_q_heads=0), -2), (dict(num_pages=0), -2), (dict(max_pages_per_req=0), -2),
     (dict(dtype=7), -3), (dict(out_dtype=1), -3), (dict(page_size=32), -6), (dict(head_dim=100), -6),
     (dict(head_dim=512), -6), (dict(path=5), -2), (dict(scale=-1.0), -2), (dict(max_spec_len=-1), -2),
+    # work that does not fit the kernels' 32-bit counters: (request, split) pairs, then units
+    (dict(batch=1 << 16, total_q=1 << 16, max_spec_len=0, max_pages_per_req=1 << 16), -6),
+    (dict(batch=1 << 14, total_q=1 << 14, max_spec_len=0, max_pages_per_req=1 << 13, n_q_heads=1024,
+          n_kv_heads=1024), -6),
 ])
 def test_attn_rejects_bad_dims(kw, code):
     d = _attn_dims(**kw)
