@@ -285,6 +285,40 @@ def test_attention_custom_scale(oracle_mod, pkg):
     assert compare_attention(out, ref, None, "f32")["max_abs_vs_f64"] <= 1e-5
 
 
+@pytest.mark.parametrize("dt,path", [("bf16", "auto"), ("f16", "auto"), ("bf16", "vector"), ("f32", "auto")])
+def test_attention_sharp_scores_with_growing_maximum(dt, path, oracle_mod, pkg):
+    """Scores of large magnitude whose running maximum keeps growing along the context: every block of
+    keys rescales the accumulators, early blocks end up weighted by 2^-100 and less, and a single late
+    token dominates some rows.  The exact result is still an ordinary softmax average (the oracle's)."""
+    import torch
+    ctx, spec = [700, 2100, 333, 64], [3, 5, 0, 7]
+    st = W.make_custom_step(4321, ctx_lens=ctx, spec_lens=spec, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                            dtype=dt, acceptance=False, name=f"sharp-{dt}")
+    rng = np.random.default_rng(99)
+    d, P = 128, 16
+    # q: all rows share a direction e (plus noise); k_t = (t / L) * amp * e + noise  =>  score grows with t
+    e = rng.standard_normal(d)
+    e /= np.linalg.norm(e)
+    q = rng.standard_normal(st.q.shape) * 0.3 + 6.0 * e
+    st.q = W.verify_step._store(q.astype(np.float32), dt)
+    kp = rng.standard_normal((st.k_pages.shape[0], 2, P, d)) * 0.5
+    for i, L in enumerate(ctx):
+        for t in range(L):
+            pg = st.block_table[i, t // P]
+            kp[pg, :, t % P, :] += (t / L) * 40.0 * e          # scale * q.k reaches ~ 6 * 40 / sqrt(128) ~ 21
+    st.k_pages = W.verify_step._store(kp.astype(np.float32), dt)
+    dev = to_device(st, acceptance=False)
+    ref, _ = oracle_mod.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
+                                    dtype=st.dtype)
+    _say(f"attn sharp scores dtype={dt} path={path}")
+    out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                          max_spec_len=max(spec), out_dtype=F32, path=path)
+    torch.cuda.synchronize()
+    rep = compare_attention(out, ref, None, dt)
+    _say(f"attn sharp {rep}")
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+
+
 ACCEPT_EDGES = [
     # spec_lens, vocab, logits dtype, temperatures
     ([0, 0, 0], 1000, "f32", 1.0),                    # plain decode only
