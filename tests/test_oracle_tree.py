@@ -6,7 +6,8 @@ masked-softmax formulation of tree attention written differently, with the mask 
 the parent pointers in Python, (iii) the fact that makes tree verification lossless -- the emitted
 tokens follow the target distribution -- by chi-square over 10^6 seeded trials, with the closed
 forms for the per-child acceptance probabilities, (iv) the greedy walk as a direct integer check,
-(v) a hand-worked residual chain (tests/golden/tree_residual_hand_example.txt).
+(v) a hand-worked residual chain (tests/golden/tree_residual_hand_example.txt), (vi) the closed
+form of repeated residuals, max(0, p - c_s q) with c_{s+1} = c_s + its mass.
 """
 import os
 
@@ -314,6 +315,32 @@ def test_hand_worked_residual_chain(oracle_mod):
                 np.array([w], np.int32), np.ones(1, np.float32), logits_dtype="f32", probs_dtype="f32")
             assert (int(path[0, 0]), int(out[0, 0])) == (want_child, want_tok), (vals, path, out)
     assert kinds == {"interval", "walk"}
+
+
+@pytest.mark.parametrize("seed,V,T", [(1, 50, 1.0), (2, 333, 0.7), (3, 1000, 1.6)])
+def test_repeated_residuals_have_a_closed_form(oracle_mod, seed, V, T):
+    """Unrolling P_s = norm(max(0, P_{s-1} - q)) gives P_s = max(0, p - c_s q) / G_s with
+    G_s = sum_v max(0, p_v - c_s q_v), c_0 = 0 and c_{s+1} = c_s + G_s (substitute and pull the positive
+    factor 1/G_s out of the max).  The oracle steps through the stages; this evaluates the closed form
+    directly and compares every token's interval width and the mass the s-th stage leaves."""
+    rng = np.random.default_rng(seed)
+    logits = rng.normal(0, 2.0, V).astype(np.float32)
+    q = _softmax64(logits.astype(np.float64) / T + rng.normal(0, 0.7, V)).astype(np.float32)
+    p = _softmax64(logits, T)
+    q64 = q.astype(np.float64)
+    c, G_prev = 0.0, 1.0
+    for s in range(0, 5):
+        g = np.maximum(0.0, p - c * q64)
+        G = g.sum()
+        assert G > 1e-6                                            # the case this form covers
+        # mass of the stage as the oracle reports it: R_s = G_s / G_{s-1} (R_0 = 1: the target distribution)
+        for t in rng.choice(V, size=12, replace=False):
+            lo, hi, R = oracle_mod.tree_cdf_interval(logits, q if s else None, logits_dtype="f32",
+                                                     probs_dtype="f32", T=T, rejections=s, t=int(t))
+            assert abs(R - G / G_prev) < 1e-12, (s, R, G / G_prev)
+            assert abs((hi - lo) / R - g[t] / G) < 1e-12, (s, t)
+            assert abs(lo / R - g[:t].sum() / G) < 1e-11, (s, t)
+        c, G_prev = c + G, G
 
 
 def test_zero_mass_residual_is_left_as_it_was(oracle_mod):
