@@ -10,8 +10,9 @@
 // Nodes the walk does not reach cost their statistics only, and a node where the first child
 // is accepted never reads its draft-probability row.
 //
-// Same procedure and per-element arithmetic as the portable node kernel (tree.hip):
-//   stage 0: P = softmax(logits / T); after each rejected child r = max(0, P - q), P = r / sum(r).
+// Same procedure as the portable node kernel (tree.hip):
+//   stage 0: P = softmax(logits / T); after each rejected child r = max(0, P - q), P = r / sum(r),
+// evaluated in its closed form (see kernel 2).
 // The row is walked by 1024 threads with 16-byte loads: element (s * 1024 + t) * 8 + e belongs
 // to step s, thread t.  A "sweep" leaves, per step, the total mass S[s] (fp32 sums over the 128
 // elements of 16 neighbouring lanes, fp64 above that); R = sum of the S[s].  The draw needs no
@@ -26,8 +27,6 @@
 #include "row_stream.h"
 
 namespace adaspec {
-
-constexpr int kHoist = 3;               // stages whose 1/R is kept in registers during a sweep
 
 __device__ __forceinline__ int sane_parent_f(int p, int j) { return j == 0 ? -1 : min(max(p, 0), j - 1); }
 
@@ -173,14 +172,18 @@ __global__ __launch_bounds__(kNT, 8) void tree_node_stats_kernel(
 }
 
 // ---- kernel 2: the walk of every request ---------------------------------------------------------
+// After s rejected children the distribution at a node is
+//     P_s = max(0, p - c_s q) / G_s,   G_s = sum_v max(0, p_v - c_s q_v),   c_0 = 0, c_{s+1} = c_s + G_s
+// (substitute P_s into r = max(0, P_s - q) and pull the positive factor 1 / G_s out of the maximum).
+// So the walk keeps two numbers per node, (c, G), and every sweep costs the same few operations per
+// element whatever the stage.  A stage whose residual has no mass leaves (c, G) as they are, and so does
+// every later stage at that node.
 struct WalkScratch {
     float  part[kNSteps][kWave];        // per step: fp32 sums of the 64 groups of 16 lanes (wave * 4 + lane / 16)
     double S[kNSteps];
     double wsum[kNW];
     float  ch_l[64], ch_q[64], ch_u[64];   // per child node: logit and draft probability of its token, its uniform
     int    ch_x[64];                    // its token
-    float  inv_r[64];                   // 1 / R_s, s = 1 ..
-    unsigned long long kept;            // bit s: stage s kept P_{s-1} (no positive part)
     unsigned long long kids;
     int fallback, hit, last_thread;
     int fallback_tot[kNW];              // (start-up only) per-wavefront row counts of the requests before this one
@@ -226,85 +229,47 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
     const char *lrow = logits, *prow = probs;
     float m = 0.f, invZ = 1.f;
 
-    // P_s at one entry from its logit and draft probability (s >= 0); inv[] = hoisted 1/R_1..
-    auto dist = [&](float l, float q, int s, const float (&inv)[kHoist], unsigned long long kept) -> float {
-        float P = __builtin_amdgcn_exp2f((l - m) * cexp) * invZ;
-#pragma unroll
-        for (int j = 1; j <= kHoist; ++j)
-            if (j <= s) P = (((kept >> j) & 1ull) ? P : fmaxf(0.f, P - q)) * inv[j - 1];
-        for (int j = kHoist + 1; j <= s; ++j)
-            P = (((kept >> j) & 1ull) ? P : fmaxf(0.f, P - q)) * sm.inv_r[j];
-        return P;
+    // max(0, p - c q) at one entry from its logit and draft probability (c = 0: p itself)
+    auto residual = [&](float l, float q, float c) -> float {
+        return fmaxf(0.f, fmaf(-c, q, __builtin_amdgcn_exp2f((l - m) * cexp) * invZ));
     };
-    // this thread's 8 masses of one step at the given stage, from the loaded words; stage 0: unnormalised
-    // 2^((l - m) c); stage >= 1: r = max(0, P_{stage-1} - q), or P_{stage-1} itself if the stage keeps it
-    auto mass8 = [&](bool in_range, const uint4 &lw, const uint4 &qw, int s_stage, bool keep_last,
-                     const float (&inv)[kHoist], unsigned long long kept, float (&rv)[8]) -> float {
+    // this thread's 8 masses of one step: before any sweep the unnormalised 2^((l - m) cexp) the node's
+    // statistics were summed from, afterwards max(0, p - c q)
+    auto mass8 = [&](bool in_range, const uint4 &lw, const uint4 &qw, bool swept, float c, float (&rv)[8]) -> float {
         float acc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) rv[e] = 0.f;
         if (in_range) {
             float x[8];
             unpack8<DT>(lw, x);
-            if (s_stage == 0) {
+            if (!swept) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) rv[e] = __builtin_amdgcn_exp2f((x[e] - m) * cexp);
             } else {
                 float q[8];
                 unpack8<DT>(qw, q);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float P = dist(x[e], q[e], s_stage - 1, inv, kept);
-                    rv[e] = keep_last ? P : fmaxf(0.f, P - q[e]);
-                }
+                for (int e = 0; e < 8; ++e) rv[e] = residual(x[e], q[e], c);
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc += rv[e];
         }
         return acc;
     };
-    // The common stages written out: stage 1..kHoist, no stage before it kept its distribution, and this
-    // one does not either.  Then r = max(0, .. max(0, max(0, p - q) / R_1 - q) / R_2 .. - q) is straight-line
-    // code: the same float operations as dist() performs, without its per-stage selects.
-    auto mass8_plain = [&](auto stage_tag, bool in_range, const uint4 &lw, const uint4 &qw,
-                           const float (&inv)[kHoist]) -> float {
-        constexpr int kStage = decltype(stage_tag)::value;
-        float acc = 0.f;
-        if (in_range) {
-            float x[8], q[8];
-            unpack8<DT>(lw, x);
-            unpack8<DT>(qw, q);
+    // one sweep over both rows: S[] and the total of max(0, p - c q)
+    auto sweep = [&](float c) -> double {
+        for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
+            float acc = 0.f;
+            if (in_range) {
+                float x[8], q[8];
+                unpack8<DT>(lw, x);
+                unpack8<DT>(qw, q);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float P = __builtin_amdgcn_exp2f((x[e] - m) * cexp) * invZ;
-#pragma unroll
-                for (int j = 1; j < kStage; ++j) P = fmaxf(0.f, P - q[e]) * inv[j - 1];
-                acc += fmaxf(0.f, P - q[e]);
+                for (int e = 0; e < 8; ++e) acc += residual(x[e], q[e], c);
             }
-        }
-        return acc;
-    };
-    // one sweep at stage >= 1 (both rows)
-    auto sweep = [&](int s_stage, bool keep_last) -> double {
-        float inv[kHoist];
-#pragma unroll
-        for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < s_stage) ? sm.inv_r[j + 1] : 1.0f;
-        const unsigned long long kept = sm.kept;
-        auto plain = [&](auto stage_tag) {
-            for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
-                const float acc = row16_sum(mass8_plain(stage_tag, in_range, lw, qw, inv));
-                if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
-            });
-        };
-        if (!keep_last && kept == 0ull && s_stage == 1) plain(std::integral_constant<int, 1>{});
-        else if (!keep_last && kept == 0ull && s_stage == 2) plain(std::integral_constant<int, 2>{});
-        else if (!keep_last && kept == 0ull && s_stage == 3) plain(std::integral_constant<int, 3>{});
-        else
-            for_each_step<true>(lrow, prow, nsteps, V, tid, [&](int s, bool in_range, const uint4 &lw, const uint4 &qw) {
-                float rv[8];
-                const float acc = row16_sum(mass8(in_range, lw, qw, s_stage, keep_last, inv, kept, rv));
-                if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
-            });
+            acc = row16_sum(acc);
+            if ((lane & 15) == 0) sm.part[s][wv * 4 + (lane >> 4)] = acc;
+        });
         return finish_sweep(sm.part, sm.S, nsteps, wv, lane);
     };
 
@@ -319,7 +284,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
         if (tid < kWave) {
             const bool is_child = lane > u && lane <= k && sane_parent_f(parents[r0 + lane], lane) == u;
             const unsigned long long kmask = __builtin_amdgcn_ballot_w64(is_child);
-            if (lane == 0) { sm.kids = kmask; sm.kept = 0ull; sm.hit = -1; sm.last_thread = -1; sm.fallback = -1; }
+            if (lane == 0) { sm.kids = kmask; sm.hit = -1; sm.last_thread = -1; sm.fallback = -1; }
             if (is_child) {
                 const int x = draft_tokens[r0 - i + lane - 1];
                 sm.ch_x[lane] = x;
@@ -332,7 +297,7 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
         }
         m = st->m;
         const int arg = st->arg;
-        double R = st->Z;
+        double R = st->Z;                                       // total of S[]
         invZ = (float)(1.0 / R);
         __syncthreads();
         unsigned long long kids = sm.kids;
@@ -346,35 +311,33 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
                 if (sm.ch_x[c] == arg) next = c;
             }
         } else {
-            int stage = 0;
-            bool keep_last = false;
+            double cd = 0.0, Gd = 1.0;                          // (c, G) of the current distribution
+            float cf = 0.f, invG = 1.f;
+            bool swept = false, frozen = false;
             while (kids != 0ull) {
                 const int c = __builtin_ctzll(kids);
                 kids &= kids - 1;
                 {   // every thread evaluates the test from the values fetched on arrival: no exchange needed
-                    float inv[kHoist];
-#pragma unroll
-                    for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 <= stage) ? sm.inv_r[j + 1] : 1.0f;
                     const float qx = sm.ch_q[c];
-                    const float px = dist(sm.ch_l[c], qx, stage, inv, sm.kept);
+                    const float px = residual(sm.ch_l[c], qx, cf) * invG;
                     const bool accepted = (qx > 0.f) ? (sm.ch_u[c] < px / qx) : true;
                     if (accepted) { next = c; break; }
                 }
-                ++stage;
-                keep_last = false;
-                R = sweep(stage, false);
-                if (!(R > 0.0)) {                               // P == q everywhere: the state stays
-                    keep_last = true;
-                    R = sweep(stage, true);
+                if (frozen) continue;                           // the residual had no mass before: it has none now
+                const double ct = cd + Gd;
+                const double Gt = sweep((float)ct);
+                if (Gt > 0.0) {
+                    cd = ct; Gd = Gt;
+                    cf = (float)ct; invG = (float)(1.0 / Gt);
+                    R = Gt;
+                } else {                                        // P == q everywhere: the state stays; S[] again
+                    frozen = true;
+                    R = sweep(cf);
                 }
-                if (tid == 0) {
-                    sm.inv_r[stage] = (float)(1.0 / R);
-                    if (keep_last) sm.kept |= 1ull << stage;
-                }
-                __syncthreads();
+                swept = true;
             }
             if (next < 0) {
-                // ---- the draw from (S, R): of the last sweep, or at stage 0 of the node's statistics ----
+                // ---- the draw from (S, R): of the last sweep, or of the node's statistics ----------------
                 const double tau = (double)uniforms[2 * (int64_t)r + 1] * R;
                 int sstar = -1, last_pos_step = 0;
                 double before = 0.0, run = 0.0, before_last = 0.0;
@@ -388,16 +351,13 @@ __global__ __launch_bounds__(kNT, 4) void accept_tree_walk_fast_kernel(
                 float rv[8];
                 float mine;
                 {
-                    float inv[kHoist];
-#pragma unroll
-                    for (int j = 0; j < kHoist; ++j) inv[j] = (j + 1 < stage) ? sm.inv_r[j + 1] : 1.0f;
                     const int v0 = (sstar * kNT + tid) * 8;
                     uint4 lw = make_uint4(0, 0, 0, 0), qw = make_uint4(0, 0, 0, 0);
                     if (v0 < V) {
                         lw = *reinterpret_cast<const uint4 *>(lrow + (int64_t)v0 * 2);
-                        if (stage > 0) qw = *reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2);
+                        if (swept) qw = *reinterpret_cast<const uint4 *>(prow + (int64_t)v0 * 2);
                     }
-                    mine = mass8(v0 < V, lw, qw, stage, keep_last, inv, sm.kept, rv);
+                    mine = mass8(v0 < V, lw, qw, swept, cf, rv);
                 }
                 // scan over the threads of that step
                 const double wi = wave_scan_incl((double)mine, lane);
