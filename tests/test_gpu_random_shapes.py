@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 
 CASES = int(os.environ.get("ADASPEC_SOAK_CASES", "6"))
 KINDS = ["chain-attention", "tree-attention", "chain-acceptance", "tree-acceptance", "draft-sampling",
-         "attention-many-rows", "acceptance-masked-padded", "kv-append"]
+         "attention-many-rows", "acceptance-masked-padded", "kv-append", "commit", "kv-compact-path"]
 
 
 def _say(msg):
@@ -158,4 +158,60 @@ def _one_case(kind, case, seed, rng, oracle_mod, pkg, torch):
                       torch.from_numpy(st.spec_lens).to("cuda:0"), max_spec_len=st.max_spec_len)
         torch.cuda.synchronize()
         assert np.array_equal(TK._bits(kp), TK._host_bits(k_ref)) and np.array_equal(TK._bits(vp), TK._host_bits(v_ref))
+    elif kind == 8:    # commit of random acceptance results (any valid lengths), token history with overflow
+        B = int(rng.integers(1, 300))
+        kmax = int(rng.integers(0, 12))
+        spec = rng.integers(0, kmax + 1, B).astype(np.int32)
+        alen = (rng.random(B) * (spec + 1)).astype(np.int32)
+        ostr = kmax + 1 + int(rng.integers(0, 3))
+        toks = -np.ones((B, ostr), np.int32)
+        for i in range(B):
+            toks[i, :alen[i] + 1] = rng.integers(0, 50000, alen[i] + 1)
+        ctx = (spec + 1 + rng.integers(0, 4000, B)).astype(np.int32)
+        nxt = rng.integers(0, 7, B).astype(np.int32)
+        cap = int(rng.integers(1, 20))
+        seq_lens = rng.integers(0, cap + 1, B).astype(np.int32)
+        seq = rng.integers(0, 1000, (B, cap)).astype(np.int32)
+        ref = KV.commit(toks, alen, spec, ctx, nxt, seq, seq_lens)
+        d = lambda a: torch.from_numpy(a).to("cuda:0")
+        seq_d, sl_d = d(seq), d(seq_lens)
+        _say(f"commit B={B} kmax={kmax} out_stride={ostr} cap={cap}")
+        com, nctx, last = pkg.commit(d(toks), d(alen), d(spec), d(ctx), max_spec_len=kmax, next_spec_lens=d(nxt),
+                                     seq_tokens=seq_d, seq_lens=sl_d)
+        torch.cuda.synchronize()
+        assert np.array_equal(com.cpu().numpy(), ref["committed_lens"])
+        assert np.array_equal(nctx.cpu().numpy(), ref["next_ctx_lens"])
+        assert np.array_equal(last.cpu().numpy(), ref["last_token"])
+        assert np.array_equal(seq_d.cpu().numpy(), ref["seq_tokens"])
+        assert np.array_equal(sl_d.cpu().numpy(), ref["seq_lens"])
+    elif kind == 9:    # compaction of a random root-to-node path of every request's tree, bit for bit
+        B = int(rng.integers(1, 24))
+        spec = rng.integers(0, int(rng.choice([4, 20, 64])), B).astype(np.int32)
+        ctx = (spec + 1 + rng.integers(0, 200, B)).astype(np.int32)
+        dt = str(rng.choice(["bf16", "f16", "f32"])); hkv = int(rng.choice([1, 2, 8])); dd = int(rng.choice([64, 128]))
+        st = W.make_custom_step(seed, ctx_lens=ctx, spec_lens=spec, n_q_heads=hkv, n_kv_heads=hkv, head_dim=dd,
+                                dtype=dt, acceptance=False, name=f"random-compact-{seed}")
+        W.attach_tree(st, max_width=int(rng.integers(1, 5)))
+        cu = st.cu_q
+        pstr = st.max_spec_len + 1 + int(rng.integers(0, 3))
+        path = -np.ones((B, pstr), np.int32)
+        alen = np.zeros(B, np.int32)
+        for i in range(B):
+            par = st.parents[cu[i]:cu[i + 1]]
+            u, walk = 0, []
+            while True:
+                kids = [c for c in range(u + 1, spec[i] + 1) if par[c] == u]
+                if not kids or rng.random() < 0.15:
+                    break
+                u = int(rng.choice(kids))
+                walk.append(u)
+            path[i, :len(walk)] = walk
+            alen[i] = len(walk)
+        k2, v2 = KV.kv_compact_path(st.k_pages, st.v_pages, st.block_table, st.ctx_lens, spec, path, alen)
+        dev = to_device(st, acceptance=False)
+        _say(f"kv_compact_path B={B} {dt} Hkv={hkv} d={dd} max k={st.max_spec_len}")
+        pkg.kv_compact_path(dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                            torch.from_numpy(path).cuda(), torch.from_numpy(alen).cuda(), max_spec_len=st.max_spec_len)
+        torch.cuda.synchronize()
+        assert np.array_equal(TK._bits(dev.k_pages), TK._host_bits(k2)) and np.array_equal(TK._bits(dev.v_pages), TK._host_bits(v2))
     return near
