@@ -22,8 +22,9 @@
  *     nothing has been enqueued.  Errors the host can see (null pointers, bad
  *     dims, unsupported dtype, misalignment, small workspace) are reported;
  *     inconsistent DEVICE data (ctx_lens[i] < n_i, page id out of range,
- *     sum(spec_lens)+batch != total_q) is undefined behaviour unless checked
- *     first with adaspec_check_ragged_inputs().
+ *     sum(spec_lens)+batch != total_q, a draft token outside [0, V)) is
+ *     undefined behaviour unless checked first with
+ *     adaspec_check_ragged_inputs() / adaspec_check_accept_inputs().
  *   - Outputs are fully overwritten.  Results are deterministic: the same
  *     inputs give bit-identical outputs (no floating-point atomics).
  *   - Host threads: the library keeps no state between calls apart from
@@ -310,6 +311,17 @@ int adaspec_verify_attn_tree(const void *q, const void *k_pages, const void *v_p
                              const int32_t *spec_lens, const int32_t *parents, void *out,
                              const adaspec_attn_dims *dims,
                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * adaspec_check_accept_inputs - optional device-side check of what the acceptance calls (chain and
+ * tree) index with: enqueues one small kernel that writes a bit mask to *err_flags (device int32):
+ * bit 0 spec_lens[i] outside [0, max_spec_len], bit 3 sum(n_i) != total_q (both as in
+ * adaspec_check_ragged_inputs), bit 5 (32) a draft token outside [0, vocab), bit 6 (64) a
+ * temperature that is negative, infinite or NaN; 0 if all is well.  The acceptance kernels read
+ * logits[x] and draft_probs[x] for every draft token x without a range check of their own.
+ */
+int adaspec_check_accept_inputs(const int32_t *draft_tokens, const int32_t *spec_lens, const float *temperature,
+                                const adaspec_accept_dims *dims, int32_t *err_flags, void *stream);
 
 /*
  * adaspec_check_tree_parents - optional device-side check of a parent array (the tree calls force

@@ -24,7 +24,7 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream":
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
     "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_resolved_path",
-    "adaspec_verify_attn_tree", "adaspec_accept_tree", "adaspec_kv_compact_path", "adaspec_check_tree_parents",
+    "adaspec_verify_attn_tree", "adaspec_accept_tree", "adaspec_kv_compact_path", "adaspec_check_tree_parents", "adaspec_check_accept_inputs",
     "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
     "adaspec_draft_sample_workspace_bytes", "adaspec_draft_sample",
     "adaspec_set_timing_events",
@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
         L.adaspec_accept_tree.argtypes = [vp] * 10 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
         L.adaspec_kv_compact_path.restype = C.c_int
         L.adaspec_kv_compact_path.argtypes = [vp] * 7 + [C.POINTER(AttnDims), C.c_int32, vp]
+        L.adaspec_check_accept_inputs.restype = C.c_int
+        L.adaspec_check_accept_inputs.argtypes = [vp, vp, vp, C.POINTER(AcceptDims), vp, vp]
         L.adaspec_check_tree_parents.restype = C.c_int
         L.adaspec_check_tree_parents.argtypes = [vp, vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]
         L.adaspec_check_ragged_inputs.restype = C.c_int
@@ -333,6 +335,23 @@ def kv_compact_path(k_pages, v_pages, block_table, ctx_lens, spec_lens, out_path
                                        _stream_ptr(stream))
     if rc != 0:
         raise AdaspecError(rc, "adaspec_kv_compact_path")
+
+
+def check_accept_inputs(draft_tokens, spec_lens, temperature, *, vocab: int, max_spec_len: int, stream=None) -> int:
+    """Runs the device-side check of the acceptance inputs and returns the flag word (synchronises)."""
+    import torch
+    for t in (draft_tokens, spec_lens):
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    assert temperature.is_cuda and temperature.dtype == torch.float32
+    B, TD = spec_lens.shape[0], draft_tokens.shape[0]
+    dims = AcceptDims(B, TD + B, TD, int(max_spec_len), int(vocab), BF16, BF16, int(max_spec_len) + 1, int(vocab),
+                      int(vocab), PATH_AUTO, 0)
+    flags = torch.zeros(1, dtype=torch.int32, device=spec_lens.device)
+    rc = lib().adaspec_check_accept_inputs(draft_tokens.data_ptr(), spec_lens.data_ptr(), temperature.data_ptr(),
+                                           C.byref(dims), flags.data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_check_accept_inputs")
+    return int(flags.item())
 
 
 def check_tree_parents(parents, spec_lens, *, max_spec_len: int, stream=None) -> int:

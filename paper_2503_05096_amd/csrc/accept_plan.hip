@@ -125,4 +125,39 @@ hipError_t launch_accept_emit(const AcceptArgs &a)
     return hipGetLastError();
 }
 
+// Device-side consistency check of the acceptance inputs (see adaspec.h).
+__global__ __launch_bounds__(256) void check_accept_inputs_kernel(
+    const int32_t *__restrict__ draft_tokens, const int32_t *__restrict__ spec_lens,
+    const float *__restrict__ temperature, int B, int total_q, int total_draft, int max_spec_len, int V,
+    int32_t *__restrict__ err_flags)
+{
+    __shared__ int s_flags, s_rows;
+    if (threadIdx.x == 0) { s_flags = 0; s_rows = 0; }
+    __syncthreads();
+    int flags = 0, rows = 0;
+    for (int i = threadIdx.x; i < B; i += blockDim.x) {
+        const int k = spec_lens[i];
+        if (k < 0 || k > max_spec_len) flags |= 1;
+        rows += k + 1;
+        const float T = temperature[i];
+        if (!(T >= 0.0f) || isinf(T)) flags |= 64;
+    }
+    for (int j = threadIdx.x; j < total_draft; j += blockDim.x) {
+        const int x = draft_tokens[j];
+        if (x < 0 || x >= V) flags |= 32;
+    }
+    atomicOr(&s_flags, flags);
+    atomicAdd(&s_rows, rows);
+    __syncthreads();
+    if (threadIdx.x == 0) *err_flags = s_flags | (s_rows != total_q ? 8 : 0);
+}
+
+hipError_t launch_check_accept_inputs(const int32_t *draft_tokens, const int32_t *spec_lens, const float *temperature,
+                                      const adaspec_accept_dims &d, int32_t *err_flags, hipStream_t stream)
+{
+    hipLaunchKernelGGL(check_accept_inputs_kernel, dim3(1), dim3(256), 0, stream, draft_tokens, spec_lens, temperature,
+                       d.batch, d.total_q, d.total_draft, d.max_spec_len, d.vocab, err_flags);
+    return hipGetLastError();
+}
+
 }  // namespace adaspec

@@ -154,6 +154,8 @@ hipError_t launch_kv_compact_path(void *k_pages, void *v_pages, const int32_t *b
                                   const int32_t *out_path, const int32_t *out_accept_len,
                                   const adaspec_attn_dims &d, int path_stride, hipStream_t stream);
 
+hipError_t launch_check_accept_inputs(const int32_t *draft_tokens, const int32_t *spec_lens, const float *temperature,
+                                      const adaspec_accept_dims &d, int32_t *err_flags, hipStream_t stream);
 hipError_t launch_check_tree_parents(const int32_t *parents, const int32_t *spec_lens, int B, int total_q,
                                      int max_spec_len, int32_t *err_flags, hipStream_t stream);
 hipError_t launch_check_ragged(const int32_t *block_table, const int32_t *ctx_lens,

@@ -387,6 +387,19 @@ int adaspec_check_ragged_inputs(const int32_t *block_table, const int32_t *ctx_l
     return ADASPEC_OK;
 }
 
+int adaspec_check_accept_inputs(const int32_t *draft_tokens, const int32_t *spec_lens, const float *temperature,
+                                const adaspec_accept_dims *dims, int32_t *err_flags, void *stream)
+{
+    int rc = validate_accept_dims(dims);
+    if (rc != ADASPEC_OK) return rc;
+    if (!spec_lens || !temperature || !err_flags) return ADASPEC_ERR_NULL;
+    if (dims->total_draft > 0 && !draft_tokens) return ADASPEC_ERR_NULL;
+    if (launch_check_accept_inputs(draft_tokens, spec_lens, temperature, *dims, err_flags,
+                                   static_cast<hipStream_t>(stream)) != hipSuccess)
+        return ADASPEC_ERR_HIP;
+    return ADASPEC_OK;
+}
+
 int adaspec_check_tree_parents(const int32_t *parents, const int32_t *spec_lens, int32_t batch, int32_t total_q,
                                int32_t max_spec_len, int32_t *err_flags, void *stream)
 {

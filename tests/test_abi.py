@@ -266,6 +266,11 @@ def test_tree_calls_validate_on_the_host():
     assert tree_acc(a, [PTR] * 10, ws=PTR + 64) == -4
     assert tree_acc(_accept_dims(batch=0, total_q=0, total_draft=0), [None] * 10, None, 0) == 0
 
+    chka = L.adaspec_check_accept_inputs
+    assert chka(PTR, None, PTR, C.byref(a), PTR, None) == -1 and chka(PTR, PTR, PTR, C.byref(a), None, None) == -1
+    assert chka(None, PTR, PTR, C.byref(a), PTR, None) == -1 and chka(PTR, PTR, PTR, None, PTR, None) == -1
+    assert chka(PTR, PTR, PTR, C.byref(_accept_dims(vocab=0)), PTR, None) == -2
+
     chk = L.adaspec_check_tree_parents
     assert chk(None, PTR, 2, 5, 3, PTR, None) == -1 and chk(PTR, PTR, 2, 5, 3, None, None) == -1
     assert chk(PTR, PTR, 2, 9, 3, PTR, None) == -2 and chk(PTR, PTR, 2, 66, 64, PTR, None) == -6

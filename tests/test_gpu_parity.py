@@ -390,6 +390,28 @@ def test_ragged_input_check(pkg):
     assert pkg.check_ragged_inputs(dev.block_table, dev.ctx_lens, sp, dims) & 1
 
 
+def test_accept_input_check(pkg):
+    import torch
+    st = W.make_custom_step(6, ctx_lens=[40, 17, 9], spec_lens=[2, 0, 3], vocab=1000, logits_dtype="bf16",
+                            temperature=[1.0, 0.0, 0.7], attention=False)
+    dev = to_device(st, attention=False)
+    kw = dict(vocab=st.vocab, max_spec_len=3)
+    _say("acceptance input check")
+    assert pkg.check_accept_inputs(dev.draft_tokens, dev.spec_lens, dev.temperature, **kw) == 0
+    for bad_tok in (-1, st.vocab, 1 << 30):
+        t = dev.draft_tokens.clone(); t[3] = bad_tok
+        assert pkg.check_accept_inputs(t, dev.spec_lens, dev.temperature, **kw) == 32
+    t = dev.draft_tokens.clone(); t[0] = st.vocab - 1
+    assert pkg.check_accept_inputs(t, dev.spec_lens, dev.temperature, **kw) == 0
+    for bad_T in (-0.5, float("inf"), float("nan")):
+        T = dev.temperature.clone(); T[2] = bad_T
+        assert pkg.check_accept_inputs(dev.draft_tokens, dev.spec_lens, T, **kw) == 64
+    sp = dev.spec_lens.clone(); sp[1] = 1
+    assert pkg.check_accept_inputs(dev.draft_tokens, sp, dev.temperature, **kw) & 8
+    sp[1] = 7
+    assert pkg.check_accept_inputs(dev.draft_tokens, sp, dev.temperature, **kw) & 1
+
+
 def test_policy_shaped_raggedness(oracle_mod, pkg):
     """spec_lens produced by the speculative-length policy itself (adaptive drafter, then draft-token
     elimination, driven by synthetic draft confidences) instead of a hand-set distribution."""
