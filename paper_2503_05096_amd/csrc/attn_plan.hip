@@ -2,6 +2,7 @@
 // the split-KV combine, and the optional device-side input check.
 #include "adaspec_internal.h"
 #include "device_utils.h"
+#include "tree_masks.h"
 
 namespace adaspec {
 
@@ -38,8 +39,22 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
     int32_t *__restrict__ cu_q, int32_t *__restrict__ split_base, int32_t *__restrict__ item_req,
     int32_t *__restrict__ item_order, int32_t *__restrict__ unit_meta, int32_t *__restrict__ row_rec,
     int W, int Hkv, int n_row_groups, int rows_per_group, int32_t *__restrict__ sched, int cus,
-    int want_cu_q)
+    int want_cu_q, const int32_t *__restrict__ parents, unsigned long long *__restrict__ anc)
 {
+    if (blockIdx.x > 0) {
+        // Tree calls (batches up to kFusedMaskMaxBatch): workgroups 1.. build the ancestor masks beside the
+        // plan, one wavefront per request.  They share nothing with workgroup 0: each wavefront adds up the
+        // rows of the requests before its own.
+        const int i = (blockIdx.x - 1) * (kPlanThreads / kWave) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+        if (i >= B) return;
+        int part = 0;
+        for (int j = lane; j < i; j += kWave) part += min(max(spec_lens[j], 0), max_spec_len) + 1;
+        const int r0 = wave_sum(part);
+        const int n = min(max(spec_lens[i], 0), max_spec_len) + 1;
+        if (r0 + n > total_q) return;                   // inconsistent metadata: leave the rows alone
+        tree_masks_of_request(parents, r0, n, lane, anc);
+        return;
+    }
     __shared__ int tot_n[kPlanThreads / kWave], tot_s[kPlanThreads / kWave];
     __shared__ int carry[2];
     __shared__ int hist[64];
@@ -226,7 +241,10 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
 hipError_t launch_attn_plan(const AttnArgs &a)
 {
     const AttnPlan &p = a.plan;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(kPlanThreads), 0, a.stream, a.ctx_lens,
+    // tree calls: one more workgroup per 16 requests for the ancestor masks (see the kernel)
+    const bool fused_masks = a.parents != nullptr && a.dims.batch <= kFusedMaskMaxBatch;
+    const int mask_wgs = fused_masks ? ceil_div(a.dims.batch, kPlanThreads / kWave) : 0;
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1 + mask_wgs), dim3(kPlanThreads), 0, a.stream, a.ctx_lens,
                        a.spec_lens, a.dims.batch, a.dims.total_q, a.dims.max_spec_len,
                        log2_exact(p.split_tokens), log2_exact(p.block_tokens), p.max_items,
                        a.dims.n_q_heads / a.dims.n_kv_heads, (int32_t *)(a.ws + p.off_header),
@@ -234,7 +252,8 @@ hipError_t launch_attn_plan(const AttnArgs &a)
                        (int32_t *)(a.ws + p.off_item_req), (int32_t *)(a.ws + p.off_item_order),
                        (int32_t *)(a.ws + p.off_unit_meta), (int32_t *)(a.ws + p.off_row_rec), a.sched_w,
                        a.dims.n_kv_heads, a.n_row_groups, a.rows_per_group, (int32_t *)(a.ws + p.off_sched),
-                       a.sched_cus, a.parents != nullptr ? 1 : 0);
+                       a.sched_cus, (a.parents != nullptr && !fused_masks) ? 1 : 0, a.parents,
+                       (unsigned long long *)(a.ws + p.off_anc));
     return hipGetLastError();
 }
 

@@ -10,16 +10,13 @@
 // the same float operations in the same order as the portable chain kernel.
 #include "adaspec_internal.h"
 #include "device_utils.h"
+#include "tree_masks.h"
 
 namespace adaspec {
 
-// A parent index as the kernels use it: the root has none (-1); anything else is forced into
-// [0, j) so that malformed input cannot send a kernel out of the request.
-__device__ __forceinline__ int sane_parent(int p, int j) { return j == 0 ? -1 : min(max(p, 0), j - 1); }
-
 // ---- ancestor masks ----------------------------------------------------------------------
-// One wavefront per request, lane j = node j.  Pointer jumping: after s rounds lane j holds the
-// nodes up to 2^s levels above it and points 2^s levels up; six rounds cover 64 nodes.
+// One wavefront per request, lane j = node j (tree_masks.h).  This kernel serves batches too large
+// for the metadata kernel's own mask workgroups; it reads the row offsets that kernel wrote.
 __global__ __launch_bounds__(256) void tree_mask_kernel(
     const int32_t *__restrict__ parents, const int32_t *__restrict__ spec_lens,
     const int32_t *__restrict__ cu_q, int B, int total_q, int max_spec_len,
@@ -30,21 +27,13 @@ __global__ __launch_bounds__(256) void tree_mask_kernel(
     const int n = min(max(spec_lens[i], 0), max_spec_len) + 1;
     const int r0 = cu_q[i];
     if (r0 < 0 || r0 + n > total_q) return;             // inconsistent metadata: leave the rows alone
-    const int p = j < n ? sane_parent(j > 0 ? parents[r0 + j] : -1, j) : -1;
-    int up = p < 0 ? j : p;                             // the root, and idle lanes, point at themselves
-    unsigned long long a = j < n ? 1ull << j : 0ull;
-#pragma unroll
-    for (int s = 0; s < 6; ++s) {
-        a |= __shfl(a, up, kWave);
-        up = __shfl(up, up, kWave);
-    }
-    if (j < n) anc[r0 + j] = a;
+    tree_masks_of_request(parents, r0, n, j, anc);
 }
 
 hipError_t launch_tree_masks(const AttnArgs &a)
 {
     const AttnPlan &p = a.plan;
-    if (a.dims.batch == 0) return hipSuccess;
+    if (a.dims.batch == 0 || a.dims.batch <= kFusedMaskMaxBatch) return hipSuccess;   // none, or built by the metadata kernel
     hipLaunchKernelGGL(tree_mask_kernel, dim3(ceil_div(a.dims.batch, 4)), dim3(256), 0, a.stream, a.parents,
                        a.spec_lens, (const int32_t *)(a.ws + p.off_cu_q), a.dims.batch, a.dims.total_q,
                        a.dims.max_spec_len, (unsigned long long *)(a.ws + p.off_anc));

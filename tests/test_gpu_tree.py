@@ -94,6 +94,19 @@ def test_tree_attention_edges(dtype, hq, hkv, d, path, oracle_mod, pkg):
     _check_tree_attention(st, oracle_mod, pkg, path=path)
 
 
+@pytest.mark.parametrize("B", [300, 2100])
+def test_tree_attention_many_requests(B, oracle_mod, pkg):
+    """More requests than one mask workgroup serves, and (2100) more than the metadata kernel builds masks
+    for itself: the separate mask kernel takes over."""
+    rng = np.random.default_rng(B)
+    spec = rng.integers(0, 9, B).astype(np.int32)
+    ctx = (spec + 1 + rng.integers(0, 70, B)).astype(np.int32)
+    st = W.make_custom_step(B, ctx_lens=ctx, spec_lens=spec, n_q_heads=4, n_kv_heads=2, head_dim=128, dtype="bf16",
+                            acceptance=False, name=f"tree-many-{B}")
+    W.attach_tree(st, max_width=3)
+    _check_tree_attention(st, oracle_mod, pkg)
+
+
 def test_chain_parents_reproduce_the_chain_call(pkg):
     import torch
     st = W.attach_tree(W.make_verify_step(3, acceptance=False, batch=24), chain=True)
