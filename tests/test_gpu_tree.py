@@ -188,6 +188,32 @@ def test_tree_accept_edges(dtype, V, oracle_mod, pkg):
     _check_tree_accept(st, oracle_mod, pkg, out_stride=70, max_near_tie_frac=0.2)
 
 
+@pytest.mark.parametrize("kpath", ["fast", "vector"])
+def test_tree_accept_residual_without_mass(kpath, oracle_mod, pkg):
+    """A draft distribution that lies above the target everywhere (each of 8 equal probabilities rounded up
+    to the next bf16 value): a child can be rejected (p/q = 0.992 < u), but max(0, P - q) is empty, so the
+    distribution stays as it was for every later child and for the draw.  Stars of 1..5 children, all
+    rejected, plus a request whose second child is accepted from the unchanged distribution."""
+    V, spec = 8, np.array([1, 3, 5, 3], np.int32)
+    st = W.make_custom_step(9, ctx_lens=spec + 1, spec_lens=spec, vocab=V, logits_dtype="bf16", temperature=1.0,
+                            attention=False, name="no-mass")
+    W.attach_tree(st, max_width=3)
+    cu = st.cu_q
+    for i in range(st.batch):
+        st.parents[cu[i] + 1:cu[i + 1]] = 0                          # stars
+    st.target_logits[:] = 0                                          # p = 1/8 everywhere (bf16 zero bits)
+    st.draft_probs[:] = W.f32_to_bf16_bits(np.full(st.draft_probs.shape, 0.1259765625, np.float32))
+    st.uniforms[:, 0] = 0.999                                        # above p/q = 0.9922...: every child rejected
+    st.uniforms[:, 1] = np.linspace(0.05, 0.95, st.total_q)
+    st.uniforms[cu[3] + 1, 0] = 0.5                                  # request 3: its second child is accepted
+    rep, (toks, alen, path) = _check_tree_accept(st, oracle_mod, pkg, kpath=kpath)
+    assert rep["exact"] == st.batch
+    assert alen.cpu().tolist() == [0, 0, 0, 1] and int(path[3, 0]) == 2
+    # the draws come from the target itself: token = floor(u1 * 8)
+    for i in range(3):
+        assert int(toks[i, 0]) == int(st.uniforms[cu[i], 1] * 8)
+
+
 def test_chain_tree_accept_equals_the_chain_call(pkg):
     import torch
     st = W.attach_tree(W.make_verify_step(2, attention=False), chain=True)
