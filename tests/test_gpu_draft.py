@@ -72,7 +72,10 @@ def _check(logits, ldt, pdt, T, u, oracle, pkg, out_rows=None, n_prob_rows=None,
     tiny = {"f32": 1e-44, "bf16": 1e-40, "f16": 6e-8}[pdt]            # subnormal quantum
     assert np.all(np.abs(q - q_ref) <= ulp_rel * np.maximum(q, q_ref) + tiny), "a stored probability is off by more than one ulp"
     frac = float(np.mean(q == q_ref))
-    assert frac >= (0.0 if pdt == "f32" else 0.999), frac
+    # 16-bit rows: at most one entry in a thousand may sit on the other side of a rounding boundary (the kernel
+    # evaluates the softmax in fp32, the oracle in fp64); tiny cases are allowed two such entries
+    if pdt != "f32":
+        assert int(np.sum(q != q_ref)) <= max(2, 0.001 * q.size), (int(np.sum(q != q_ref)), q.size)
     near = 0
     for r in range(R):
         assert 0 <= tok[r] < V and conf[r] == q[r, tok[r]] and (T[r] == 0 or conf[r] > 0)
