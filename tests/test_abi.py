@@ -284,3 +284,19 @@ def test_tree_calls_validate_on_the_host():
     assert compact(d, [PTR + 8] + [PTR] * 6) == -4
     assert compact(_attn_dims(head_dim=4), [PTR] * 7) == -6                 # rows are moved in 16-byte pieces
     assert compact(_attn_dims(batch=0, total_q=0), [None] * 7) == 0
+
+
+# ------------------------------------------------------------------ the headers themselves
+@pytest.mark.parametrize("header", ["adaspec.h", "adaspec_policy.h"])
+def test_headers_are_plain_c(header, tmp_path):
+    """The boundary is a C ABI: each header compiles on its own as C99 with warnings as errors."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    src = tmp_path / "t.c"
+    src.write_text(f'#include "{header}"\nint main(void) {{ return 0; }}\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", f"-I{inc}", str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
