@@ -160,18 +160,25 @@ def _stream_ptr(stream) -> int:
     return int(s.cuda_stream)
 
 
-# Default workspace, one per device, grown on demand.  Callers that issue calls on several streams must
-# pass their own `workspace` per stream: calls that share a workspace have to be ordered on one stream.
+# Default workspaces: one per (device, call family), grown on demand.  Attention, acceptance and draft
+# sampling never share one (a planned attention pass keeps its metadata in its workspace across calls).
+# A buffer that is outgrown stays referenced until the process ends: a kernel on a caller-supplied,
+# non-current stream may still be using it, and torch's allocator would hand a freed block to the next
+# tensor at once.  Callers that issue calls on several streams must pass their own `workspace` per
+# stream: calls that share a workspace have to be ordered on one stream.
 _ws_cache = {}
+_ws_retired = []
 
 
-def _workspace(nbytes: int, device, workspace):
+def _workspace(nbytes: int, device, workspace, family: str):
     import torch
     if workspace is not None:
         return workspace
-    key = (str(device),)
+    key = (str(device), family)
     ws = _ws_cache.get(key)
     if ws is None or ws.numel() < nbytes:
+        if ws is not None:
+            _ws_retired.append(ws)
         ws = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
         _ws_cache[key] = ws
     return ws
@@ -193,7 +200,9 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d].
 
     plan: "run" (build the ragged metadata, then run), "build" (metadata only; returns None) or
-    "reuse" (run with the metadata a previous call left in the same workspace).
+    "reuse" (run with the metadata a previous call left in the same workspace).  "build" and "reuse"
+    require `workspace`: a tensor of at least adaspec_verify_attn_workspace_bytes that the caller owns
+    and that no other call touches between the build and the last reuse.
     parents [TQ] int32 (a draft tree): adaspec_verify_attn_tree instead."""
     import torch
     dims = attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
@@ -209,7 +218,12 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     if need == 0 and dims.batch > 0:
         raise AdaspecError(L.adaspec_verify_attn(None, None, None, None, None, None, None, C.byref(dims),
                                                  None, 0, None) or -2, "adaspec_verify_attn (dims)")
-    ws = _workspace(need, q.device, workspace)
+    if plan != "run" and workspace is None:
+        # the metadata of a planned pass lives in the workspace between the calls: it has to be the
+        # caller's own buffer, one that nothing else writes to meanwhile
+        raise ValueError("verify_attn(plan='build' / 'reuse') needs an explicit workspace= tensor that the "
+                         "caller keeps for the whole pass")
+    ws = _workspace(need, q.device, workspace, "attn")
     if parents is not None:
         assert parents.is_cuda and parents.is_contiguous() and parents.dtype == torch.int32
         assert parents.shape == (q.shape[0],)
@@ -276,7 +290,7 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
         out_accept_len = torch.empty((B,), dtype=torch.int32, device=target_logits.device)
     L = lib()
     need = L.adaspec_accept_workspace_bytes(C.byref(dims))
-    ws = _workspace(max(need, 256), target_logits.device, workspace)
+    ws = _workspace(max(need, 256), target_logits.device, workspace, "accept")
     rc = L.adaspec_accept(target_logits.data_ptr(), pp, tp, uniforms.data_ptr(), spec_lens.data_ptr(),
                           temperature.data_ptr(), out_tokens.data_ptr(), out_accept_len.data_ptr(),
                           C.byref(dims), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
@@ -306,7 +320,7 @@ def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spe
         out_path = torch.empty((B, out_stride), dtype=torch.int32, device=dev)
     L = lib()
     need = L.adaspec_accept_workspace_bytes(C.byref(dims))
-    ws = _workspace(max(need, 256), dev, workspace)
+    ws = _workspace(max(need, 256), dev, workspace, "accept")
     rc = L.adaspec_accept_tree(target_logits.data_ptr(), pp, tp, parents.data_ptr(), uniforms.data_ptr(),
                                spec_lens.data_ptr(), temperature.data_ptr(), out_tokens.data_ptr(),
                                out_accept_len.data_ptr(), out_path.data_ptr(), C.byref(dims), ws.data_ptr(),
@@ -451,7 +465,7 @@ def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft
                      draft_probs.stride(0), PATH_TWO_PASS if path == "split" else _PATHS[path], 0)
     L = lib()
     need = L.adaspec_draft_sample_workspace_bytes(C.byref(dims))
-    ws = _workspace(need, dev, workspace) if need else None
+    ws = _workspace(need, dev, workspace, "draft") if need else None
     rc = L.adaspec_draft_sample(draft_logits.data_ptr(), temperature.data_ptr(), uniforms.data_ptr(),
                                 None if out_rows is None else out_rows.data_ptr(), draft_probs.data_ptr(),
                                 draft_tokens.data_ptr(), confidence.data_ptr(), C.byref(dims),

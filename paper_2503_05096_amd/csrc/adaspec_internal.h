@@ -20,7 +20,7 @@ struct AttnPlan {
     int   max_items;        // host-side bound on the number of work items
     int   max_rows;         // (max_spec_len + 1) * G
     // byte offsets into the workspace
-    size_t off_header;      // int32[16]: [0] n_items, [1] ticket counter, [2] rounds of the static schedule
+    size_t off_header;      // int32[16]: [0] n_items, [1] unused, [2] rounds of the static schedule
     size_t off_cu_q;        // int32[B + 1]
     size_t off_split_base;  // int32[B + 1]: first item of each request
     size_t off_item_req;    // int32[max_items]

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(
     if (tid == 0) {
         if (!fast) { cu_q[B] = carry[0]; split_base[B] = carry[1]; }
         header[0] = min(carry[1], max_items);   // number of work items
-        header[1] = 0;                          // ticket counter of the vector kernel
+        header[1] = 0;                          // (unused)
     }
     // Schedule order: longest items first (counting sort on the length in token blocks), so that
     // the workgroups that take units last get the short items and the tail of the launch is short.

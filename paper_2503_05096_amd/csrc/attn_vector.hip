@@ -20,7 +20,7 @@ template <class T>
 __global__ __launch_bounds__(64) void attn_vector_kernel(
     const void *__restrict__ q, const void *__restrict__ k_pages, const void *__restrict__ v_pages,
     const int32_t *__restrict__ block_table, const int32_t *__restrict__ ctx_lens,
-    const int32_t *__restrict__ spec_lens, void *__restrict__ out, int32_t *__restrict__ header,
+    const int32_t *__restrict__ spec_lens, void *__restrict__ out, const int32_t *__restrict__ header,
     const int32_t *__restrict__ cu_q, const int32_t *__restrict__ split_base,
     const int32_t *__restrict__ item_req, const int32_t *__restrict__ item_order,
     const unsigned long long *__restrict__ anc, float *__restrict__ part_ml, float *__restrict__ part_o,
@@ -34,11 +34,9 @@ __global__ __launch_bounds__(64) void attn_vector_kernel(
     const int n_items = header[0];
     const int total_units = n_items * Hkv * n_row_chunks;
 
-    for (;;) {
-        int ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&header[1], 1);
-        ticket = __shfl(ticket, 0, kWave);
-        if (ticket >= total_units) break;
+    // Units are handed out statically (longest items first, strided over the grid): the metadata holds
+    // no counter that a launch would use up, so a caller may reuse it for any number of layers.
+    for (int ticket = blockIdx.x; ticket < total_units; ticket += gridDim.x) {
         const int rc = ticket % n_row_chunks;
         const int g = (ticket / n_row_chunks) % Hkv;
         const int item = item_order[ticket / (n_row_chunks * Hkv)];
@@ -175,7 +173,7 @@ hipError_t launch_attn_vector(const AttnArgs &a)
         using T = decltype(tag);
         hipLaunchKernelGGL(attn_vector_kernel<T>, dim3(grid), dim3(64), 0, a.stream, a.q, a.k_pages,
                            a.v_pages, a.block_table, a.ctx_lens, a.spec_lens, a.out,
-                           (int32_t *)(a.ws + p.off_header), (const int32_t *)(a.ws + p.off_cu_q),
+                           (const int32_t *)(a.ws + p.off_header), (const int32_t *)(a.ws + p.off_cu_q),
                            (const int32_t *)(a.ws + p.off_split_base),
                            (const int32_t *)(a.ws + p.off_item_req),
                            (const int32_t *)(a.ws + p.off_item_order),

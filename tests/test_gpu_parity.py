@@ -486,6 +486,48 @@ def test_attention_plan_reuse_across_layers(pkg):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"layer {layer}"
 
 
+@pytest.mark.parametrize("shape", ["cfg1-f32-d64", "bf16-forced-vector"])
+def test_attention_plan_reuse_on_the_vector_path(shape, pkg):
+    """The metadata of the vector kernel holds nothing a launch uses up: a build followed by several
+    reuse calls, and a self-contained run followed by a reuse of what it left, all equal a fresh
+    self-contained call bit for bit."""
+    import torch
+    if shape == "cfg1-f32-d64":
+        st, path = W.make_verify_step(1, acceptance=False, poison=False), "auto"
+    else:
+        st, path = W.make_verify_step(3, acceptance=False, poison=False, batch=12), "vector"
+    dev = to_device(st, acceptance=False)
+    kw = dict(max_spec_len=st.max_spec_len, path=path)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    ws2 = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    _say(f"attn vector-path plan reuse {shape} B={st.batch}")
+    args = (dev.block_table, dev.ctx_lens, dev.spec_lens)
+    assert pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, *args, plan="build", workspace=ws, **kw) is None
+    g = torch.Generator(device="cuda:0").manual_seed(5)
+    for layer in range(4):
+        q = torch.randn(dev.q.shape, generator=g, device="cuda:0").to(dev.q.dtype)
+        a = pkg.verify_attn(q, dev.v_pages, dev.k_pages, *args, plan="reuse", workspace=ws, **kw)
+        b = pkg.verify_attn(q, dev.v_pages, dev.k_pages, *args, workspace=ws2, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b), f"build + reuse, layer {layer}"
+    # a self-contained run leaves reusable metadata behind as well
+    first = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, *args, workspace=ws, **kw)
+    again = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, *args, plan="reuse", workspace=ws, **kw)
+    fresh = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, *args, workspace=ws2, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(first, fresh) and torch.equal(again, fresh)
+
+
+def test_planned_pass_needs_the_callers_own_workspace(pkg):
+    """The Python wrapper refuses plan='build' / 'reuse' on its shared default workspace."""
+    st = W.make_verify_step(1, acceptance=False, poison=False)
+    dev = to_device(st, acceptance=False)
+    for plan in ("build", "reuse"):
+        with pytest.raises(ValueError):
+            pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
+                            max_spec_len=st.max_spec_len, plan=plan)
+
+
 @pytest.mark.parametrize("accept_path", ["auto", "two_pass"])
 def test_step_replayed_from_a_hip_graph(accept_path, pkg):
     """The two calls of a step captured into one HIP graph (the library launches kernels only: no

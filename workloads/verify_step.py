@@ -329,7 +329,7 @@ def make_verify_step(cfg: int, *, greedy: bool = False, batch: Optional[int] = N
     name = CONFIGS[cfg]["name"] + ("-greedy" if greedy else "")
     return _build(name, seed, ctx, k, T, streams=ss[3:], attention=attention,
                   acceptance=acceptance, poison=poison, sharp_key=sharp_key,
-                  planted_ties=planted_ties, **spec)
+                  planted_ties=planted_ties, masked_frac=masked_frac, **spec)
 
 
 def make_custom_step(seed: int, ctx_lens, spec_lens, *, n_q_heads=8, n_kv_heads=8, head_dim=64,
