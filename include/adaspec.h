@@ -209,6 +209,28 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const adaspec_accept_dims *dims,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * adaspec_accept_noalloc - adaspec_accept for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without workspace / workspace_bytes), same kernels, same outputs bit for
+ * bit.  What the workspace would hold lives in a device array of ADASPEC_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's code object: every GPU the library runs on holds it from the first use until
+ * the process ends.  The call allocates and frees nothing and synchronises nothing.
+ *   - dims whose adaspec_accept_workspace_bytes exceeds ADASPEC_NOALLOC_SCRATCH_BYTES are rejected
+ *     with ADASPEC_ERR_WORKSPACE before anything is enqueued (use adaspec_accept for those).
+ *   - All calls on one GPU share that GPU's array: calls that can overlap in time on one GPU (other
+ *     streams, other threads) race on it; order them on one stream.  The array keeps the previous
+ *     call's contents; the kernels initialise whatever they rely on.
+ *   - The first call on a device looks the array's address up (no allocation); a caller that captures
+ *     graphs makes one call outside a capture first.  More than 64 devices: ADASPEC_ERR_UNSUPPORTED.
+ */
+#define ADASPEC_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+int adaspec_accept_noalloc(const void *target_logits, const void *draft_probs,
+                           const int32_t *draft_tokens, const float *uniforms,
+                           const int32_t *spec_lens, const float *temperature,
+                           int32_t *out_tokens, int32_t *out_accept_len,
+                           const adaspec_accept_dims *dims, void *stream);
+
 /* The kernel path adaspec_accept takes for these dims and base pointers (the pointers are only
  * looked at for their alignment): ADASPEC_PATH_VECTOR, _FAST, _STREAM or _TWO_PASS; dims->path
  * itself unless it is ADASPEC_PATH_AUTO; a negative adaspec_status if dims are invalid or a

@@ -23,7 +23,7 @@ _PATHS = {"auto": PATH_AUTO, "vector": PATH_VECTOR, "fast": PATH_FAST, "stream":
 
 EXPORTS = (
     "adaspec_verify_attn_workspace_bytes", "adaspec_verify_attn",
-    "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_resolved_path",
+    "adaspec_accept_workspace_bytes", "adaspec_accept", "adaspec_accept_noalloc", "adaspec_accept_resolved_path",
     "adaspec_verify_attn_tree", "adaspec_accept_tree", "adaspec_kv_compact_path", "adaspec_check_tree_parents", "adaspec_check_accept_inputs",
     "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
     "adaspec_draft_sample_workspace_bytes", "adaspec_draft_sample",
@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
         L.adaspec_accept_workspace_bytes.argtypes = [C.POINTER(AcceptDims)]
         L.adaspec_accept.restype = C.c_int
         L.adaspec_accept.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp, C.c_size_t, vp]
+        L.adaspec_accept_noalloc.restype = C.c_int
+        L.adaspec_accept_noalloc.argtypes = [vp] * 8 + [C.POINTER(AcceptDims), vp]
         L.adaspec_accept_resolved_path.restype = C.c_int
         L.adaspec_accept_resolved_path.argtypes = [vp, vp, C.POINTER(AcceptDims)]
         L.adaspec_verify_attn_tree.restype = C.c_int
@@ -297,6 +299,28 @@ def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temper
     if rc != 0:
         raise AdaspecError(rc, "adaspec_accept")
     return out_tokens, out_accept_len
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def accept_noalloc(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, out_tokens,
+                   out_accept_len, *, max_spec_len: int, out_stride: Optional[int] = None, path: str = "auto",
+                   stream=None) -> None:
+    """adaspec_accept_noalloc: acceptance into the caller's output tensors, on the library's built-in
+    scratch memory.  Nothing is allocated here either: the outputs are required arguments."""
+    import torch
+    assert uniforms.is_cuda and uniforms.is_contiguous() and uniforms.dtype == torch.float32
+    assert temperature.is_cuda and temperature.dtype == torch.float32
+    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    assert out_tokens.is_cuda and out_tokens.dtype == torch.int32 and out_tokens.is_contiguous()
+    assert tuple(out_tokens.shape) == (dims.batch, dims.out_stride)
+    assert out_accept_len.is_cuda and out_accept_len.dtype == torch.int32 and tuple(out_accept_len.shape) == (dims.batch,)
+    rc = lib().adaspec_accept_noalloc(target_logits.data_ptr(), pp, tp, uniforms.data_ptr(), spec_lens.data_ptr(),
+                                      temperature.data_ptr(), out_tokens.data_ptr(), out_accept_len.data_ptr(),
+                                      C.byref(dims), _stream_ptr(stream))
+    if rc != 0:
+        raise AdaspecError(rc, "adaspec_accept_noalloc")
 
 
 def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spec_lens, temperature, *,

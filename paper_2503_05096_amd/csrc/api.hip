@@ -5,6 +5,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "adaspec_internal.h"
 #include "device_utils.h"
 
@@ -12,6 +14,33 @@ namespace adaspec {
 
 static hipEvent_t g_ev_start[3] = {nullptr, nullptr, nullptr};
 static hipEvent_t g_ev_stop[3] = {nullptr, nullptr, nullptr};
+
+// ---- scratch memory of adaspec_accept_noalloc ------------------------------------------------------
+// A file-scope device array stands in for the workspace argument: every GPU the library runs on holds
+// its own copy, at its own address, until the process ends.  In host code the NAME of the array is
+// only a handle for hipGetSymbolAddress; the device address it yields (looked up once per device,
+// with that device current) is what kernels, and anything else that touches the memory, are given.
+constexpr size_t kNoallocScratchBytes = ADASPEC_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (ADASPEC_OK), or a negative status
+static int noalloc_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return ADASPEC_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ADASPEC_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ADASPEC_OK;
+}
 
 // compute units of the current device (asked once; 256 if the runtime cannot tell)
 static int compute_units()
@@ -254,20 +283,28 @@ int adaspec_accept_resolved_path(const void *target_logits, const void *draft_pr
     return resolve_accept_path(*dims, target_logits, draft_probs);
 }
 
-int adaspec_accept(const void *target_logits, const void *draft_probs,
-                   const int32_t *draft_tokens, const float *uniforms,
-                   const int32_t *spec_lens, const float *temperature,
-                   int32_t *out_tokens, int32_t *out_accept_len,
-                   const adaspec_accept_dims *dims,
-                   void *workspace, size_t workspace_bytes, void *stream)
+// workspace == NULL with use_static_scratch: the library's own device array takes its place
+static int accept_impl(const void *target_logits, const void *draft_probs,
+                       const int32_t *draft_tokens, const float *uniforms,
+                       const int32_t *spec_lens, const float *temperature,
+                       int32_t *out_tokens, int32_t *out_accept_len,
+                       const adaspec_accept_dims *dims,
+                       void *workspace, size_t workspace_bytes, bool use_static_scratch, void *stream)
 {
     int rc = validate_accept_dims(dims);
     if (rc != ADASPEC_OK) return rc;
+    if (use_static_scratch && make_accept_plan(*dims).total_bytes > kNoallocScratchBytes)
+        return ADASPEC_ERR_WORKSPACE;           // larger than the built-in scratch: use adaspec_accept
     if (dims->batch == 0) return ADASPEC_OK;
     if (!target_logits || !uniforms || !spec_lens || !temperature || !out_tokens || !out_accept_len ||
-        !workspace)
+        (!workspace && !use_static_scratch))
         return ADASPEC_ERR_NULL;
     if (dims->total_draft > 0 && (!draft_probs || !draft_tokens)) return ADASPEC_ERR_NULL;
+    if (use_static_scratch) {
+        rc = noalloc_scratch(&workspace);
+        if (rc != ADASPEC_OK) return rc;
+        workspace_bytes = kNoallocScratchBytes;
+    }
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ADASPEC_ERR_ALIGN;
     const int path = resolve_accept_path(*dims, target_logits, draft_probs);
     if (path < 0) return path;
@@ -304,6 +341,27 @@ int adaspec_accept(const void *target_logits, const void *draft_probs,
         return ADASPEC_ERR_HIP;
     if (launch_accept_emit(a) != hipSuccess) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
+}
+
+int adaspec_accept(const void *target_logits, const void *draft_probs,
+                   const int32_t *draft_tokens, const float *uniforms,
+                   const int32_t *spec_lens, const float *temperature,
+                   int32_t *out_tokens, int32_t *out_accept_len,
+                   const adaspec_accept_dims *dims,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return accept_impl(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, out_tokens,
+                       out_accept_len, dims, workspace, workspace_bytes, false, stream);
+}
+
+int adaspec_accept_noalloc(const void *target_logits, const void *draft_probs,
+                           const int32_t *draft_tokens, const float *uniforms,
+                           const int32_t *spec_lens, const float *temperature,
+                           int32_t *out_tokens, int32_t *out_accept_len,
+                           const adaspec_accept_dims *dims, void *stream)
+{
+    return accept_impl(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, out_tokens,
+                       out_accept_len, dims, nullptr, 0, true, stream);
 }
 
 int adaspec_accept_tree(const void *target_logits, const void *draft_probs,

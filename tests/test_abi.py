@@ -300,3 +300,21 @@ def test_headers_are_plain_c(header, tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", f"-I{inc}", str(src)],
                        capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_accept_noalloc_rejects_on_the_host():
+    """The entry point without a workspace validates like adaspec_accept, and refuses dims whose workspace
+    would not fit its built-in scratch array, all before any HIP call."""
+    from paper_2503_05096_amd.binding import NOALLOC_SCRATCH_BYTES
+    L = pkg.lib()
+    call = lambda d, ptrs=None: L.adaspec_accept_noalloc(*([PTR] * 8 if ptrs is None else ptrs), C.byref(d), None)
+    assert call(_accept_dims(vocab=0)) == -2
+    assert call(_accept_dims(logits_dtype=9)) == -3
+    assert call(_accept_dims(), [None] + [PTR] * 7) == -1
+    B = 200000
+    big = _accept_dims(batch=B, total_q=2 * B, total_draft=B, max_spec_len=1, out_stride=2)
+    assert L.adaspec_accept_workspace_bytes(C.byref(big)) > NOALLOC_SCRATCH_BYTES
+    assert call(big) == -5
+    header = open(HEADER).read()
+    assert re.search(r"#define\s+ADASPEC_NOALLOC_SCRATCH_BYTES\s+\(\(size_t\)8\s*<<\s*20\)", header)
+    assert NOALLOC_SCRATCH_BYTES == 8 << 20
