@@ -95,20 +95,20 @@ struct AcceptPlan {
     size_t off_row_cand;    // int32[TQ]  token to emit if the request stops at this row
     size_t off_row_meta;    // int32[TQ][8]: request, position j, k, draft token, temperature bits, draft row
     // two-pass form
-    size_t off_row_stat;    // RowStat[TQ]: (m, Z) of the sampled draft rows, from the first pass
-    size_t off_req_pick;    // int2[B]: (deciding row, accepted drafts) of each request
-    size_t off_half_stat;   // HalfStat[B][4]: per part of the row
-    size_t off_part;        // float[B][16 steps][16][2][4]: partial sums of the split second pass (B <= kSplitMaxBatch)
+    size_t off_row_stat;    // RowStat[TQ]: (m, Z) of the sampled draft rows, from the first pass (one workgroup per row)
+    size_t off_req_ticket;  // int32[B]: workgroups of the second pass that have finished, per request
+    size_t off_slot_rec;    // int32[B * max_spec_len][4] per (request, draft position): token, its logit, its draft
+                            // probability, the accept uniform (form in parts)
+    size_t off_part_stat;   // HalfStat[B * max_spec_len][8]: (maximum, normaliser | arg-max) of each part of a draft row
+    size_t off_half_stat;   // HalfStat[B][16]: per part of the deciding row
+    size_t off_part;        // float[B][16 parts][4 steps][4][2][4]: partial sums of the deciding rows
     size_t off_tree_stat;   // tree acceptance: per-node statistics (tree_node_stat_bytes() each)
     size_t total_bytes;
 };
 // p_v = 2^((l_v - m) c) / Z of a row (first pass of the two-pass form -> second pass)
 struct RowStat { float m; float pad; double Z; };
-// per (request, half row) of the split second pass: (m, Z) the half's sums are relative to; for a greedy
-// bonus row (maximum, arg-max or -1)
+// per part of a row: (m, Z) the part's sums are relative to; for a greedy row (maximum, arg-max or -1)
 struct HalfStat { float m; int arg; double Z; };
-// the split second pass keeps partial sums per request in the workspace: set up for batches up to
-constexpr int kSplitMaxBatch = 256;
 AcceptPlan make_accept_plan(const adaspec_accept_dims &d);
 bool accept_fast_path_supported(const adaspec_accept_dims &d, const void *logits, const void *probs);
 
@@ -134,10 +134,13 @@ hipError_t launch_accept_stream(const AcceptArgs &a);
 // two-pass form: flags of the draft rows, then one workgroup per request (sampling + outputs)
 hipError_t launch_accept_test(const AcceptArgs &a);
 hipError_t launch_accept_resolve(const AcceptArgs &a);
-// second pass with the deciding row of each request cut into four parts + the pick kernel (batch <= kSplitMaxBatch)
-bool accept_split_supported(const adaspec_accept_dims &d);
-size_t accept_split_part_bytes(int batch);
-hipError_t launch_accept_split(const AcceptArgs &a);
+// two-pass form with every row cut into parts (accept_parts.hip): up to 1024 requests
+bool accept_parts_supported(const adaspec_accept_dims &d);
+size_t accept_parts_slot_bytes(const adaspec_accept_dims &d);
+size_t accept_parts_stat_bytes(const adaspec_accept_dims &d);
+size_t accept_parts_sum_bytes(const adaspec_accept_dims &d);
+size_t accept_parts_sum_stat_bytes(const adaspec_accept_dims &d);
+hipError_t launch_accept_parts(const AcceptArgs &a);
 
 // tree verification (tree.hip, tree_fast.hip): every node's acceptance, then the walk; needs the accept plan's cu_q / row_req
 // portable form (any types and sizes): a per-node kernel writes (next node or -1, token if the walk stops here)

@@ -159,10 +159,12 @@ AcceptPlan make_accept_plan(const adaspec_accept_dims &d)
     p.off_row_cand = off; off = align_up(off + tq * 4, 256);
     p.off_row_meta = off; off = align_up(off + tq * 32, 256);
     const size_t nb = (size_t)(d.batch > 0 ? d.batch : 1);
-    p.off_row_stat = off;  off = align_up(off + tq * sizeof(RowStat), 256);
-    p.off_req_pick = off;  off = align_up(off + nb * sizeof(int2), 256);
-    p.off_half_stat = off; off = align_up(off + nb * 4 * sizeof(HalfStat), 256);
-    p.off_part = off;      off = align_up(off + (d.batch <= kSplitMaxBatch ? accept_split_part_bytes((int)nb) : 0), 256);
+    p.off_row_stat = off;   off = align_up(off + tq * sizeof(RowStat), 256);
+    p.off_req_ticket = off; off = align_up(off + nb * 4, 256);
+    p.off_slot_rec = off;   off = align_up(off + accept_parts_slot_bytes(d), 256);
+    p.off_part_stat = off;  off = align_up(off + accept_parts_stat_bytes(d), 256);
+    p.off_half_stat = off;  off = align_up(off + accept_parts_sum_stat_bytes(d), 256);
+    p.off_part = off;       off = align_up(off + accept_parts_sum_bytes(d), 256);
     p.off_tree_stat = off; off = align_up(off + tq * tree_node_stat_bytes(), 256);
     p.total_bytes = off;
     return p;
@@ -320,13 +322,17 @@ static int accept_impl(const void *target_logits, const void *draft_probs,
     a.stream = static_cast<hipStream_t>(stream);
 
     if (two_pass) {
-        // the flags of the draft rows, then one workgroup per request: sampling on the one row that
-        // decides its token, and the request's outputs (no emit kernel)
+        // the statistics of the draft rows, then per request the accept tests, the sampling on the one row
+        // that decides its token, and the request's outputs (no emit kernel); both in row parts for up to
+        // 1024 requests, larger batches with one workgroup per row and then per request
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
-        if (launch_accept_test(a) != hipSuccess) return ADASPEC_ERR_HIP;
-        if ((accept_split_supported(*dims) ? launch_accept_split(a) : launch_accept_resolve(a)) != hipSuccess)
-            return ADASPEC_ERR_HIP;
+        if (accept_parts_supported(*dims)) {
+            if (launch_accept_parts(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        } else {
+            if (launch_accept_test(a) != hipSuccess) return ADASPEC_ERR_HIP;
+            if (launch_accept_resolve(a) != hipSuccess) return ADASPEC_ERR_HIP;
+        }
         if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
             return ADASPEC_ERR_HIP;
         return ADASPEC_OK;
