@@ -28,10 +28,8 @@
  *   - Outputs are fully overwritten.  Results are deterministic: the same
  *     inputs give bit-identical outputs (no floating-point atomics).
  *   - Host threads: the library keeps no state between calls apart from
- *     one-time device queries and the timing hooks of
- *     adaspec_set_timing_events (process-wide, meant for a single-threaded
- *     benchmark).  Calls from several threads are safe as long as they do not
- *     share a workspace.  The calls enqueue kernels only (no allocation, no
+ *     one-time device queries.  Calls from several threads are safe as long
+ *     as they do not share a workspace.  The calls enqueue kernels only (no allocation, no
  *     memset, no synchronisation), so they can be captured into a HIP graph.
  *     The first call of a kernel path on a device does its one-time set-up
  *     (occupancy and device queries; the streaming and two-pass acceptance
@@ -103,6 +101,11 @@ typedef struct {
     int32_t path;               /* adaspec_path                                         */
     float   scale;              /* softmax scale; 0 means 1/sqrt(head_dim)              */
     int32_t plan_mode;          /* adaspec_plan_mode (below); 0 for a self-contained call */
+    void   *timing_start;       /* optional pair of hipEvent_t (both or neither, NULL = none):      */
+    void   *timing_stop;        /* recorded on `stream` right before / right after the call's main
+                                   kernel (not the metadata kernel, not the split-KV combine), for
+                                   callers that want the kernel's own duration.  Events belong to
+                                   the caller, who must keep them alive until they have completed. */
 } adaspec_attn_dims;
 
 /* The ragged metadata of a verification pass (row offsets, KV-split work list, schedule)
@@ -175,6 +178,9 @@ typedef struct {
     int64_t probs_row_stride;   /* elements between draft_probs rows, >= V             */
     int32_t path;               /* adaspec_path                                        */
     int32_t reserved;
+    void   *timing_start;       /* optional pair of hipEvent_t (both or neither, NULL = none), recorded */
+    void   *timing_stop;        /* on `stream` around the call's acceptance kernels (two-pass form: both
+                                   passes; per-row forms: the row kernel, not the emit kernel)          */
 } adaspec_accept_dims;
 
 size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims);
@@ -449,6 +455,8 @@ typedef struct {
                                    form when it fits, a workspace is given and
                                    V >= 32768, else FAST when it fits, else VECTOR */
     int32_t reserved;
+    void   *timing_start;       /* optional pair of hipEvent_t (both or neither, NULL = none), recorded */
+    void   *timing_stop;        /* on `stream` around the call's kernels                                */
 } adaspec_draft_dims;
 
 /* Bytes of workspace the split form needs for these dims (0 if it does not apply). */
@@ -463,14 +471,6 @@ int adaspec_draft_sample(const void *draft_logits,      /* [R][V]               
                          float *confidence,             /* [R]                                  */
                          const adaspec_draft_dims *dims,
                          void *workspace, size_t workspace_bytes, void *stream);
-
-/* ------------------------------------------------------------------------
- * Per-kernel timing for benchmarks: when both events are non-NULL, the next
- * calls record `start` (hipEvent_t) right before and `stop` right after the
- * launch of the selected kernel on the call's stream.  Pass NULLs to clear.
- * which: 0 = attention main kernel, 1 = accept main kernel, 2 = draft sampling kernel.
- * ---------------------------------------------------------------------- */
-int adaspec_set_timing_events(int which, void *start_event, void *stop_event);
 
 const char *adaspec_status_string(int status);
 int adaspec_version(void);

@@ -77,6 +77,14 @@ int adaspec_policy_eliminate(const adaspec_time_model *m, int32_t batch,
                              const double *ar, double tpot,
                              int32_t *spec_lens_out, double *goodput_out);
 
+/* The two counts of Eq. 4 for ONE target pass over a ragged batch: *n_b = sum (spec_lens[i] + 1), the
+ * verified positions, and *n_c = the context tokens they are charged: every position its own context,
+ * sum_i sum_{j=1..k_i+1} (C_i + j - 1), as printed (verify_ctx_once == 0), or every request's context
+ * once, sum_i (C_i + k_i + 1) (verify_ctx_once != 0; see adaspec_time_model).  What the offline analyzer
+ * regresses its measured times on.  ADASPEC_ERR_DIM for a negative length. */
+int adaspec_policy_count_tokens(int32_t batch, const int32_t *ctx_committed, const int32_t *spec_lens,
+                                int32_t verify_ctx_once, double *n_c, double *n_b);
+
 /* Offline analyzer (Sec. 6): least-squares fit of (alpha, gamma, delta) of Eq. 2 to n measured
  * forward passes with n_c[i] context tokens, n_b[i] batch tokens and time t[i].
  * ADASPEC_ERR_DIM if n < 3 or the three columns are linearly dependent. */

@@ -70,6 +70,20 @@ def t_verify(m: TimeModel, C: Sequence[int], k: Sequence[int]) -> float:
     return t_fwd(m.alpha_v, m.gamma_v, m.delta_v, n_c, n_b)
 
 
+def count_tokens(C: Sequence[int], k: Sequence[int], verify_ctx_once: bool = False) -> Tuple[int, int]:
+    """(N_c, N_b) of Eq. 4, counted position by position: N_b = number of verified positions; N_c = context
+    tokens before each position, summed over positions (as printed), or each request's C_i + k_i + 1 once."""
+    n_c = n_b = 0
+    for c, ki in zip(C, k):
+        for j in range(1, int(ki) + 2):
+            n_b += 1
+            if not verify_ctx_once:
+                n_c += int(c) + j - 1
+        if verify_ctx_once:
+            n_c += int(c) + int(ki) + 1
+    return n_c, n_b
+
+
 def estimate_time(m: TimeModel, C, draft_steps: int, k) -> float:
     """Eq. 1: T_sd = T_d + T_v."""
     return t_draft(m, C, draft_steps) + t_verify(m, C, k)

@@ -7,5 +7,5 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     AdaspecError, AttnDims, AcceptDims, CommitDims, accept, accept_noalloc, accept_resolved_path, verify_attn, check_ragged_inputs,
     kv_append, commit, draft_sample, DraftDims, accept_tree, kv_compact_path, check_tree_parents, check_accept_inputs,
-    set_timing_events, status_string, version, lib,
+    status_string, version, lib, accept_dims, attn_dims,
 )

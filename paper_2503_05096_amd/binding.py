@@ -27,7 +27,6 @@ EXPORTS = (
     "adaspec_verify_attn_tree", "adaspec_accept_tree", "adaspec_kv_compact_path", "adaspec_check_tree_parents", "adaspec_check_accept_inputs",
     "adaspec_check_ragged_inputs", "adaspec_kv_append", "adaspec_commit",
     "adaspec_draft_sample_workspace_bytes", "adaspec_draft_sample",
-    "adaspec_set_timing_events",
     "adaspec_status_string", "adaspec_version",
 )
 
@@ -37,7 +36,8 @@ class AttnDims(C.Structure):
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_size", C.c_int32), ("num_pages", C.c_int32), ("max_pages_per_req", C.c_int32),
                 ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("path", C.c_int32),
-                ("scale", C.c_float), ("plan_mode", C.c_int32)]
+                ("scale", C.c_float), ("plan_mode", C.c_int32),
+                ("timing_start", C.c_void_p), ("timing_stop", C.c_void_p)]
 
 
 class AcceptDims(C.Structure):
@@ -45,7 +45,8 @@ class AcceptDims(C.Structure):
                 ("max_spec_len", C.c_int32), ("vocab", C.c_int32), ("logits_dtype", C.c_int32),
                 ("probs_dtype", C.c_int32), ("out_stride", C.c_int32),
                 ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64),
-                ("path", C.c_int32), ("reserved", C.c_int32)]
+                ("path", C.c_int32), ("reserved", C.c_int32),
+                ("timing_start", C.c_void_p), ("timing_stop", C.c_void_p)]
 
 
 class CommitDims(C.Structure):
@@ -56,7 +57,8 @@ class CommitDims(C.Structure):
 class DraftDims(C.Structure):
     _fields_ = [("rows", C.c_int32), ("vocab", C.c_int32), ("logits_dtype", C.c_int32),
                 ("probs_dtype", C.c_int32), ("logits_row_stride", C.c_int64), ("probs_row_stride", C.c_int64),
-                ("path", C.c_int32), ("reserved", C.c_int32)]
+                ("path", C.c_int32), ("reserved", C.c_int32),
+                ("timing_start", C.c_void_p), ("timing_stop", C.c_void_p)]
 
 
 class AdaspecError(RuntimeError):
@@ -115,8 +117,6 @@ def lib() -> C.CDLL:
         L.adaspec_draft_sample.argtypes = [vp] * 7 + [C.POINTER(DraftDims), vp, C.c_size_t, vp]
         L.adaspec_draft_sample_workspace_bytes.restype = C.c_size_t
         L.adaspec_draft_sample_workspace_bytes.argtypes = [C.POINTER(DraftDims)]
-        L.adaspec_set_timing_events.restype = C.c_int
-        L.adaspec_set_timing_events.argtypes = [C.c_int, vp, vp]
         L.adaspec_status_string.restype = C.c_char_p
         L.adaspec_status_string.argtypes = [C.c_int]
         L.adaspec_version.restype = C.c_int
@@ -186,6 +186,16 @@ def _workspace(nbytes: int, device, workspace, family: str):
     return ws
 
 
+def _with_timing(dims, timing):
+    """timing = (start, stop): raw hipEvent_t handles (ints or c_void_p) the library records around the call's
+    main kernel(s) on the call's stream; None = no events."""
+    if timing is not None:
+        start, stop = timing
+        dims.timing_start = start.value if isinstance(start, C.c_void_p) else start
+        dims.timing_stop = stop.value if isinstance(stop, C.c_void_p) else stop
+    return dims
+
+
 def attn_dims(q, k_pages, block_table, *, max_spec_len: int, scale: float = 0.0,
               out_dtype: Optional[int] = None, path: str = "auto", plan: str = "run") -> AttnDims:
     dt = _dtype_code(q)
@@ -198,7 +208,7 @@ def attn_dims(q, k_pages, block_table, *, max_spec_len: int, scale: float = 0.0,
 
 def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None, *,
                 max_spec_len: int, scale: float = 0.0, out_dtype: Optional[int] = None,
-                path: str = "auto", plan: str = "run", workspace=None, stream=None, parents=None):
+                path: str = "auto", plan: str = "run", workspace=None, stream=None, parents=None, timing=None):
     """adaspec_verify_attn on device tensors; returns `out` [TQ][Hq][d].
 
     plan: "run" (build the ragged metadata, then run), "build" (metadata only; returns None) or
@@ -207,8 +217,8 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     and that no other call touches between the build and the last reuse.
     parents [TQ] int32 (a draft tree): adaspec_verify_attn_tree instead."""
     import torch
-    dims = attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
-                     out_dtype=out_dtype, path=path, plan=plan)
+    dims = _with_timing(attn_dims(q, k_pages, block_table, max_spec_len=max_spec_len, scale=scale,
+                                  out_dtype=out_dtype, path=path, plan=plan), timing)
     for t in (q, k_pages, v_pages, block_table, ctx_lens, spec_lens):
         assert t.is_cuda and t.is_contiguous()
     assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32 and spec_lens.dtype == torch.int32
@@ -245,7 +255,7 @@ def verify_attn(q, k_pages, v_pages, block_table, ctx_lens, spec_lens, out=None,
     return out
 
 
-def _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path):
+def accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path):
     """(dims, draft_probs pointer, draft_tokens pointer) of an acceptance call: marshalling only."""
     import torch
     TQ, V = target_logits.shape
@@ -269,7 +279,7 @@ def _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_l
 def accept_resolved_path(target_logits, draft_probs, draft_tokens, spec_lens, *, max_spec_len: int,
                          out_stride: Optional[int] = None, path: str = "auto") -> str:
     """adaspec_accept_resolved_path: the kernel path adaspec_accept takes for these tensors."""
-    dims, pp, _ = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    dims, pp, _ = accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
     rc = lib().adaspec_accept_resolved_path(target_logits.data_ptr(), pp, C.byref(dims))
     if rc < 0:
         raise AdaspecError(rc, "adaspec_accept_resolved_path")
@@ -278,13 +288,14 @@ def accept_resolved_path(target_logits, draft_probs, draft_tokens, spec_lens, *,
 
 def accept(target_logits, draft_probs, draft_tokens, uniforms, spec_lens, temperature, *,
            max_spec_len: int, out_tokens=None, out_accept_len=None, out_stride: Optional[int] = None,
-           path: str = "auto", workspace=None, stream=None) -> Tuple[object, object]:
+           path: str = "auto", workspace=None, stream=None, timing=None) -> Tuple[object, object]:
     """adaspec_accept on device tensors; returns (out_tokens [B][out_stride], out_accept_len [B])."""
     import torch
     for t in (uniforms, temperature):
         assert t.is_cuda
     assert uniforms.is_contiguous() and uniforms.dtype == torch.float32 and temperature.dtype == torch.float32
-    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    dims, pp, tp = accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    _with_timing(dims, timing)
     B, out_stride = dims.batch, dims.out_stride
     if out_tokens is None:
         out_tokens = torch.empty((B, out_stride), dtype=torch.int32, device=target_logits.device)
@@ -312,7 +323,7 @@ def accept_noalloc(target_logits, draft_probs, draft_tokens, uniforms, spec_lens
     import torch
     assert uniforms.is_cuda and uniforms.is_contiguous() and uniforms.dtype == torch.float32
     assert temperature.is_cuda and temperature.dtype == torch.float32
-    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    dims, pp, tp = accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
     assert out_tokens.is_cuda and out_tokens.dtype == torch.int32 and out_tokens.is_contiguous()
     assert tuple(out_tokens.shape) == (dims.batch, dims.out_stride)
     assert out_accept_len.is_cuda and out_accept_len.dtype == torch.int32 and tuple(out_accept_len.shape) == (dims.batch,)
@@ -325,7 +336,7 @@ def accept_noalloc(target_logits, draft_probs, draft_tokens, uniforms, spec_lens
 
 def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spec_lens, temperature, *,
                 max_spec_len: int, out_tokens=None, out_accept_len=None, out_path=None,
-                out_stride: Optional[int] = None, path: str = "auto", workspace=None, stream=None):
+                out_stride: Optional[int] = None, path: str = "auto", workspace=None, stream=None, timing=None):
     """adaspec_accept_tree; returns (out_tokens [B][out_stride], out_accept_len [B], out_path [B][out_stride]).
     path: "auto", "vector" (portable per-node kernel) or "fast" (1024-thread per-node kernel)."""
     import torch
@@ -333,7 +344,8 @@ def accept_tree(target_logits, draft_probs, draft_tokens, parents, uniforms, spe
         assert t.is_cuda and t.is_contiguous()
     assert uniforms.dtype == torch.float32 and temperature.dtype == torch.float32 and parents.dtype == torch.int32
     assert parents.shape == (target_logits.shape[0],)
-    dims, pp, tp = _accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    dims, pp, tp = accept_dims(target_logits, draft_probs, draft_tokens, spec_lens, max_spec_len, out_stride, path)
+    _with_timing(dims, timing)
     B, out_stride = dims.batch, dims.out_stride
     dev = target_logits.device
     if out_tokens is None:
@@ -469,7 +481,7 @@ def commit(out_tokens, out_accept_len, spec_lens, ctx_lens, *, max_spec_len: int
 
 
 def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft_probs=None, out_rows=None,
-                 draft_tokens=None, confidence=None, path: str = "auto", workspace=None, stream=None):
+                 draft_tokens=None, confidence=None, path: str = "auto", workspace=None, stream=None, timing=None):
     """adaspec_draft_sample; returns (draft_probs, draft_tokens [R] int32, confidence [R] float32).
     path "split" (ADASPEC_PATH_TWO_PASS for this call) cuts every row into four parts."""
     import torch
@@ -487,6 +499,7 @@ def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft
         confidence = torch.empty((R,), dtype=torch.float32, device=dev)
     dims = DraftDims(R, V, _dtype_code(draft_logits), _dtype_code(draft_probs), draft_logits.stride(0),
                      draft_probs.stride(0), PATH_TWO_PASS if path == "split" else _PATHS[path], 0)
+    _with_timing(dims, timing)
     L = lib()
     need = L.adaspec_draft_sample_workspace_bytes(C.byref(dims))
     ws = _workspace(need, dev, workspace, "draft") if need else None
@@ -498,9 +511,3 @@ def draft_sample(draft_logits, temperature, uniforms, *, probs_dtype=None, draft
     if rc != 0:
         raise AdaspecError(rc, "adaspec_draft_sample")
     return draft_probs, draft_tokens, confidence
-
-
-def set_timing_events(which: int, start_event_ptr: Optional[int], stop_event_ptr: Optional[int]) -> None:
-    rc = lib().adaspec_set_timing_events(int(which), start_event_ptr, stop_event_ptr)
-    if rc != 0:
-        raise AdaspecError(rc, "adaspec_set_timing_events")

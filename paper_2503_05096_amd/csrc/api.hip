@@ -1,7 +1,8 @@
 // C ABI entry points of libadaspec.so: host-side validation, workspace layout
-// and the launch sequence of each call.  No HIP call is made before the
-// arguments have been validated, so the error paths work on a machine with no
-// GPU.
+// and the launch sequence of each call.  The entry points that enqueue work make
+// no HIP call before their arguments have been validated, so their error paths
+// work on a machine with no GPU (adaspec_accept_resolved_path asks the device for
+// its compute-unit count; without a device it assumes 256).
 #include <math.h>
 #include <string.h>
 
@@ -12,8 +13,12 @@
 
 namespace adaspec {
 
-static hipEvent_t g_ev_start[3] = {nullptr, nullptr, nullptr};
-static hipEvent_t g_ev_stop[3] = {nullptr, nullptr, nullptr};
+// the optional event pair of a dims struct: recorded only if both are given
+static bool record_event(void *start, void *stop, bool first, hipStream_t stream)
+{
+    if (!start || !stop) return true;
+    return hipEventRecord(static_cast<hipEvent_t>(first ? start : stop), stream) == hipSuccess;
+}
 
 // ---- scratch memory of adaspec_accept_noalloc ------------------------------------------------------
 // A file-scope device array stands in for the workspace argument: every GPU the library runs on holds
@@ -218,12 +223,10 @@ static int verify_attn_impl(const void *q, const void *k_pages, const void *v_pa
         if (tree && launch_tree_masks(a) != hipSuccess) return ADASPEC_ERR_HIP;
     }
     if (plan_only) return ADASPEC_OK;
-    if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_start[0], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, true, a.stream)) return ADASPEC_ERR_HIP;
     hipError_t e = fast ? launch_attn_mfma(a) : launch_attn_vector(a);
     if (e != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[0] && g_ev_stop[0] && hipEventRecord(g_ev_stop[0], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, false, a.stream)) return ADASPEC_ERR_HIP;
     if (launch_attn_combine(a) != hipSuccess) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
@@ -325,26 +328,22 @@ static int accept_impl(const void *target_logits, const void *draft_probs,
         // the statistics of the draft rows, then per request the accept tests, the sampling on the one row
         // that decides its token, and the request's outputs (no emit kernel); both in row parts for up to
         // 1024 requests, larger batches with one workgroup per row and then per request
-        if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
-            return ADASPEC_ERR_HIP;
+        if (!record_event(dims->timing_start, dims->timing_stop, true, a.stream)) return ADASPEC_ERR_HIP;
         if (accept_parts_supported(*dims)) {
             if (launch_accept_parts(a) != hipSuccess) return ADASPEC_ERR_HIP;
         } else {
             if (launch_accept_test(a) != hipSuccess) return ADASPEC_ERR_HIP;
             if (launch_accept_resolve(a) != hipSuccess) return ADASPEC_ERR_HIP;
         }
-        if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
-            return ADASPEC_ERR_HIP;
+        if (!record_event(dims->timing_start, dims->timing_stop, false, a.stream)) return ADASPEC_ERR_HIP;
         return ADASPEC_OK;
     }
     // the register-resident kernel finds each row's request itself; only the vector kernel needs the plan
     if (!fast && !streaming && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, true, a.stream)) return ADASPEC_ERR_HIP;
     hipError_t e = fast ? launch_accept_fast(a) : (streaming ? launch_accept_stream(a) : launch_accept_vector(a));
     if (e != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, false, a.stream)) return ADASPEC_ERR_HIP;
     if (launch_accept_emit(a) != hipSuccess) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
@@ -403,16 +402,14 @@ int adaspec_accept_tree(const void *target_logits, const void *draft_probs,
     a.stream = static_cast<hipStream_t>(stream);
     // (the fast kernels find their rows and requests themselves, up to a few thousand requests)
     if ((!fast || tree_fast_needs_plan(*dims)) && launch_accept_plan(a) != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_start[1], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, true, a.stream)) return ADASPEC_ERR_HIP;
     if (fast) {
         if (launch_accept_tree_fast(a, parents, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
     } else {
         if (launch_accept_tree_nodes(a, parents) != hipSuccess) return ADASPEC_ERR_HIP;
         if (launch_accept_tree_walk(a, out_path) != hipSuccess) return ADASPEC_ERR_HIP;
     }
-    if (g_ev_start[1] && g_ev_stop[1] && hipEventRecord(g_ev_stop[1], a.stream) != hipSuccess)
-        return ADASPEC_ERR_HIP;
+    if (!record_event(dims->timing_start, dims->timing_stop, false, a.stream)) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
 
@@ -570,7 +567,7 @@ int adaspec_draft_sample(const void *draft_logits, const float *temperature, con
     }
     const bool fast = !split && fast_ok && d->path != ADASPEC_PATH_VECTOR;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_start[2], st) != hipSuccess) return ADASPEC_ERR_HIP;
+    if (!record_event(d->timing_start, d->timing_stop, true, st)) return ADASPEC_ERR_HIP;
     hipError_t e;
     if (split)
         e = launch_draft_split(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens, confidence, *d,
@@ -580,15 +577,7 @@ int adaspec_draft_sample(const void *draft_logits, const float *temperature, con
     else
         e = launch_draft_sample(draft_logits, temperature, uniforms, out_rows, draft_probs, draft_tokens, confidence, *d, st);
     if (e != hipSuccess) return ADASPEC_ERR_HIP;
-    if (g_ev_start[2] && g_ev_stop[2] && hipEventRecord(g_ev_stop[2], st) != hipSuccess) return ADASPEC_ERR_HIP;
-    return ADASPEC_OK;
-}
-
-int adaspec_set_timing_events(int which, void *start_event, void *stop_event)
-{
-    if (which < 0 || which > 2) return ADASPEC_ERR_DIM;
-    g_ev_start[which] = static_cast<hipEvent_t>(start_event);
-    g_ev_stop[which] = static_cast<hipEvent_t>(stop_event);
+    if (!record_event(d->timing_start, d->timing_stop, false, st)) return ADASPEC_ERR_HIP;
     return ADASPEC_OK;
 }
 

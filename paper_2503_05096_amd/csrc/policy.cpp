@@ -164,6 +164,24 @@ int adaspec_policy_eliminate(const adaspec_time_model *m, int32_t B, const int32
     return ADASPEC_OK;
 }
 
+int adaspec_policy_count_tokens(int32_t B, const int32_t *C, const int32_t *spec_lens, int32_t verify_ctx_once,
+                                double *n_c, double *n_b)
+{
+    if (!n_c || !n_b || (B > 0 && (!C || !spec_lens))) return ADASPEC_ERR_NULL;
+    if (B < 0) return ADASPEC_ERR_DIM;
+    adaspec_time_model m = {};
+    m.verify_ctx_once = verify_ctx_once ? 1 : 0;
+    double c = 0.0, b = 0.0;
+    for (int i = 0; i < B; ++i) {
+        if (spec_lens[i] < 0 || C[i] < 0) return ADASPEC_ERR_DIM;
+        c += verify_ctx(m, C[i], spec_lens[i]);
+        b += spec_lens[i] + 1.0;
+    }
+    *n_c = c;
+    *n_b = b;
+    return ADASPEC_OK;
+}
+
 int adaspec_policy_fit_time_model(int32_t n, const double *n_c, const double *n_b, const double *t,
                                   double *alpha, double *gamma, double *delta)
 {

@@ -15,7 +15,7 @@ from . import binding
 
 EXPORTS = (
     "adaspec_policy_estimate_time", "adaspec_policy_goodput", "adaspec_policy_adaptive_draft",
-    "adaspec_policy_eliminate", "adaspec_policy_fit_time_model",
+    "adaspec_policy_eliminate", "adaspec_policy_fit_time_model", "adaspec_policy_count_tokens",
 )
 
 
@@ -42,6 +42,8 @@ def _lib():
         L.adaspec_policy_adaptive_draft.argtypes = [C.POINTER(TimeModel), i32, vp, vp, i32, dbl, dbl, vp, vp, vp]
         L.adaspec_policy_eliminate.restype = C.c_int
         L.adaspec_policy_eliminate.argtypes = [C.POINTER(TimeModel), i32, vp, i32, vp, dbl, vp, vp]
+        L.adaspec_policy_count_tokens.restype = C.c_int
+        L.adaspec_policy_count_tokens.argtypes = [i32, vp, vp, i32, vp, vp]
         L.adaspec_policy_fit_time_model.restype = C.c_int
         L.adaspec_policy_fit_time_model.argtypes = [i32, vp, vp, vp, vp, vp, vp]
         _ready = True
@@ -101,6 +103,18 @@ def eliminate(m: TimeModel, ctx_committed, draft_steps: int, ar, tpot: float = f
     if rc != 0:
         raise binding.AdaspecError(rc, "adaspec_policy_eliminate")
     return k, float(g.value)
+
+
+def count_tokens(ctx_committed, spec_lens, verify_ctx_once: bool = False) -> Tuple[float, float]:
+    """(N_c, N_b) of Eq. 4 for one target pass (adaspec_policy_count_tokens)."""
+    c, k = _i32(ctx_committed), _i32(spec_lens)
+    assert len(c) == len(k)
+    n_c, n_b = C.c_double(0.0), C.c_double(0.0)
+    rc = _lib().adaspec_policy_count_tokens(len(c), _p(c), _p(k), int(bool(verify_ctx_once)), C.addressof(n_c),
+                                            C.addressof(n_b))
+    if rc != 0:
+        raise binding.AdaspecError(rc, "adaspec_policy_count_tokens")
+    return float(n_c.value), float(n_b.value)
 
 
 def fit_time_model(n_c, n_b, t) -> Tuple[float, float, float]:

@@ -156,8 +156,6 @@ def test_accept_resolved_path_of_forced_paths():
 
 def test_misc_entry_points_validate():
     L = pkg.lib()
-    assert L.adaspec_set_timing_events(3, None, None) == -2
-    assert L.adaspec_set_timing_events(0, None, None) == 0
     assert L.adaspec_check_ragged_inputs(None, PTR, PTR, C.byref(_attn_dims()), PTR, None) == -1
     assert L.adaspec_check_ragged_inputs(PTR, PTR, PTR, C.byref(_attn_dims(batch=-1)), PTR, None) == -2
     assert "unknown" in pkg.status_string(-99)

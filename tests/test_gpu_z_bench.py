@@ -45,3 +45,24 @@ def test_bench_line_tree():
     _check_common(d)
     assert d["config"]["workload"].endswith("-tree3") and d["config"]["tree"]["max_children_per_node"] == 3
     assert "walk" in d["config"]["accept_kernel_path"]
+
+
+def test_bench_line_default_has_every_config():
+    """The default line (what the driver records): the headline workload, the benchmark's other
+    configurations and the policy-shaped batch, each with its step time and fractions."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "12", "--warmup", "3"],
+                       capture_output=True, text=True, timeout=580)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    assert d["config"]["workload"] == "cfg3-llama3-8b-gqa" and d["steps"] == 12
+    assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["value"] > 0 and d["cpu_baseline"]["cores"] >= 1
+    assert d["accept_vs_oracle"]["hard_mismatches"] == 0
+    assert set(d["other_configs"]) == {"cfg2", "cfg4", "cfg4g", "cfg5"}
+    for name, o in d["other_configs"].items():
+        assert o["ms_per_step"] > 0 and 0.02 < o["attention_frac"] < 1.0 and 0.0 < o["accept_frac"] < 1.0, (name, o)
+        assert o["accept_vs_oracle"]["hard_mismatches"] == 0, (name, o)
+    p = d["policy_preset"]
+    assert p["workload"].endswith("-policy") and p["draft_steps"] >= 1 and p["accept_vs_oracle"]["hard_mismatches"] == 0
+    assert sum(p["spec_len_histogram"]) == p["batch"]

@@ -202,3 +202,49 @@ def test_library_policy_argument_errors():
         PP.fit_time_model([1, 2], [1, 2], [1, 2])                     # n < 3
     with pytest.raises(Exception):
         PP.fit_time_model([1, 2, 3], [2, 4, 6], [1, 2, 3])            # dependent columns
+
+
+# ------------------------------------------------------------------ Eq. 4 token counts
+def test_token_counts_of_eq4_by_hand_and_closed_form():
+    # three requests with caches 10, 200, 33 and 2, 0, 1 drafts: positions see 10,11,12 | 200 | 33,34
+    assert OP.count_tokens([10, 200, 33], [2, 0, 1]) == (33 + 200 + 67, 6)
+    # every request's cache once for all its positions: (10+3) + (200+1) + (33+2)
+    assert OP.count_tokens([10, 200, 33], [2, 0, 1], verify_ctx_once=True) == (249, 6)
+    rng = np.random.default_rng(4)
+    C, k = rng.integers(0, 5000, 40), rng.integers(0, 9, 40)
+    n_c, n_b = OP.count_tokens(C, k)
+    assert n_b == int((k + 1).sum())
+    assert n_c == int(((k + 1) * C + k * (k + 1) // 2).sum())          # arithmetic series per request
+    # the time model charges exactly these counts
+    tv = OP.t_verify(M, C, k)
+    assert math.isclose(tv, M.alpha_v * n_c + M.gamma_v * n_b + M.delta_v, rel_tol=1e-13)
+
+
+def test_library_token_counts_equal_the_oracle():
+    rng = np.random.default_rng(5)
+    for once in (False, True):
+        for B in (0, 1, 7, 300):
+            C, k = rng.integers(0, 100000, B), rng.integers(0, 65, B)
+            got = PP.count_tokens(C, k, verify_ctx_once=once)
+            assert got == tuple(float(v) for v in OP.count_tokens(C, k, verify_ctx_once=once))
+    with pytest.raises(Exception):
+        PP.count_tokens([5], [-1])
+
+
+def test_shipped_time_model_record_is_complete_and_feeds_the_policy():
+    """The MI355X record the analyzer wrote (paper_2503_05096_amd/data): both verification fits and the
+    draft fit are there, and the policy, library and oracle alike, runs on them to the same decisions."""
+    import workloads as W
+    from paper_2503_05096_amd import analyzer
+    for once in (False, True):
+        lm = analyzer.load_time_model(verify_ctx_once=once)
+        assert lm.alpha_d > 0 and lm.delta_d > 0 and lm.alpha_v > 0 and lm.delta_v > 0 and lm.verify_ctx_once == int(once)
+        om = OP.TimeModel(lm.alpha_d, lm.gamma_d, lm.delta_d, lm.alpha_v, lm.gamma_v, lm.delta_v, bool(once))
+        pin = W.policy_inputs(3, batch=48)
+        for tpot in (float("inf"), 2.5e-3):
+            steps, ar, g = PP.adaptive_draft(lm, pin["ctx_committed"], pin["conf"], pin["prev_conf"], tpot)
+            o_steps, o_ars, _ = OP.adaptive_drafter(om, pin["ctx_committed"], pin["conf"], pin["prev_conf"], tpot)
+            assert steps == o_steps
+            k, gk = PP.eliminate(lm, pin["ctx_committed"], steps, ar, tpot)
+            o_k, o_g = OP.eliminate(om, pin["ctx_committed"], o_steps, o_ars, tpot)
+            assert np.array_equal(k, o_k) and math.isclose(gk, o_g, rel_tol=1e-12)

@@ -13,6 +13,8 @@ from .verify_step import (  # noqa: F401
     VerifyStep,
     make_verify_step,
     make_custom_step,
+    policy_inputs,
+    make_policy_step,
     attach_tree,
     f32_to_bf16_bits,
     bf16_bits_to_f32,

@@ -332,6 +332,37 @@ def make_verify_step(cfg: int, *, greedy: bool = False, batch: Optional[int] = N
                   planted_ties=planted_ties, masked_frac=masked_frac, **spec)
 
 
+def policy_inputs(cfg: int = 3, *, batch: Optional[int] = None, max_steps: int = 8,
+                  seed: Optional[int] = None) -> Dict[str, object]:
+    """Synthetic inputs of the speculative-length policy for one step of config `cfg` (random draws only;
+    the policy itself is not evaluated here): the committed context lengths C_i (the config's context
+    distribution, read as the cache BEFORE the step), the temperatures, and a table of draft-model
+    confidences conf[s][i] for up to max_steps draft steps.  Every request has its own draft quality
+    a_i ~ U(0.35, 0.97); its confidences are Beta(8 a_i, 8 (1 - a_i)) draws, so acceptance rates fall off
+    at different speeds across the batch, which is what makes per-request lengths differ."""
+    seed = 5096100 + cfg if seed is None else seed
+    ss = np.random.SeedSequence(seed).spawn(5)
+    ctx, _, T = _ragged(cfg, False, ss[0], ss[1], ss[2], batch)
+    B = len(ctx)
+    g = np.random.Generator(np.random.PCG64(ss[3]))
+    quality = g.uniform(0.35, 0.97, B)
+    conf = np.clip(g.beta(8.0 * quality, 8.0 * (1.0 - quality), size=(max_steps, B)), 1e-3, 1.0)
+    return {"ctx_committed": ctx.astype(np.int32), "temperature": T, "conf": conf.astype(np.float64),
+            "prev_conf": float(quality.mean()), "seed": seed, "cfg": cfg}
+
+
+def make_policy_step(pin: Dict[str, object], spec_lens, **kw) -> VerifyStep:
+    """The verification step of a batch whose per-request draft lengths `spec_lens` came out of the policy
+    for the inputs `pin` (policy_inputs): the config's tensors, ctx_lens = C_i + k_i + 1."""
+    cfg = int(pin["cfg"])
+    k = np.asarray(spec_lens, dtype=np.int32)
+    ctx = (np.asarray(pin["ctx_committed"]) + k + 1).astype(np.int32)
+    ss = np.random.SeedSequence(int(pin["seed"]) + 7).spawn(11)
+    spec = {kk: v for kk, v in CONFIGS[cfg].items() if kk != "name"}
+    return _build(CONFIGS[cfg]["name"] + "-policy", int(pin["seed"]), ctx, k, np.asarray(pin["temperature"], np.float32),
+                  streams=ss[3:], **spec, **kw)
+
+
 def make_custom_step(seed: int, ctx_lens, spec_lens, *, n_q_heads=8, n_kv_heads=8, head_dim=64,
                      dtype="f32", vocab=1024, logits_dtype="f32", temperature=1.0,
                      logits_sigma=2.0, noise_sigma=1.0, draft_temp=1.0, name="custom",
