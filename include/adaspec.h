@@ -425,7 +425,11 @@ int adaspec_kv_compact_path(void *k_pages, void *v_pages, const int32_t *block_t
  *           sum of the ROUNDED row exceeds uniforms[r] * (sum of the rounded
  *           row), so a token of probability zero is never drawn;
  *   T == 0: greedy drafting: token = argmax(logits) (lowest index on ties) and
- *           q = softmax(logits) (temperature 1), rounded and stored;
+ *           q = softmax(logits) (temperature 1), rounded and stored.  The token
+ *           is then NOT a draw from the stored row: such a draft must be
+ *           verified at temperature 0 as well (adaspec_accept with
+ *           temperature[i] == 0 never looks at q); verified at T > 0 the
+ *           emitted tokens would no longer follow the target's distribution;
  *   confidence[r] = q[token] as stored, widened to float.
  * The row is written to draft_probs row out_rows[r] (row r if out_rows is
  * NULL), so a caller can place it directly into the ragged [TD][V] layout

@@ -89,7 +89,7 @@ def _check(logits, ldt, pdt, T, u, oracle, pkg, out_rows=None, n_prob_rows=None,
         assert lo - NEAR * Q <= tau < hi + NEAR * Q, f"row {r}: token {tok[r]} vs {tok_ref[r]} is not a near-tie"
         near += 1
     _say(f"draft_sample ok: bit-equal fraction {frac:.6f}, near-ties {near}/{R}")
-    assert near <= max(2, 0.05 * R)
+    assert near <= max(2, 0.025 * R)          # measured: none on these shapes
     return frac, near
 
 

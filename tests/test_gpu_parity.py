@@ -2,8 +2,13 @@
 same seeded inputs, through the C ABI.  Tolerances:
 
   attention   max |gpu - oracle_f64| <= 2e-3 on the fp32 accumulator output
-              (out_dtype = fp32); the 16-bit output must be that accumulator
-              rounded once to nearest-even, bit for bit.
+              (out_dtype = fp32): the benchmark's bar.  The tests hold the
+              kernels to a much tighter regression guard per storage type, a
+              few times what they deliver (bf16 1.2e-6 with the softmax weights
+              fed as hi + lo, fp16 2.3e-4 at contexts of 16..33 tokens, fp32
+              1e-6): a kernel that lost two digits must not stay green.  The
+              16-bit output must be that accumulator rounded once to
+              nearest-even, bit for bit.
   acceptance  tokens and accept lengths bit-exact except counted near-ties
               (see tests/harness.py); greedy rows have no tolerance at all.
 """
@@ -18,7 +23,9 @@ from tests.harness import compare_accept, compare_attention, to_device
 
 pytestmark = pytest.mark.gpu
 
-ATTN_TOL = 2e-3
+ATTN_TOL = 2e-3                                             # the benchmark's bar
+ATTN_GUARD = {"f32": 2e-5, "bf16": 2e-5, "f16": 1e-3}       # what the tests enforce (<= the bar)
+NEAR_TIE_FRAC = 0.025                                       # near-tie budget: 3 x the measured 1 in 128 requests
 F32 = 0
 
 
@@ -35,7 +42,7 @@ def _round_like(x32, dtype):
     return x32.to({"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[dtype])
 
 
-def check_attention(st, oracle, pkg, path="auto", tol=ATTN_TOL):
+def check_attention(st, oracle, pkg, path="auto", tol=None):
     import torch
     dev = to_device(st, acceptance=False)
     ref, ref_r = oracle.verify_attn(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens,
@@ -46,7 +53,8 @@ def check_attention(st, oracle, pkg, path="auto", tol=ATTN_TOL):
                           out_dtype=F32, **kw)
     torch.cuda.synchronize()
     rep = compare_attention(acc, ref, None, st.dtype)
-    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= tol, rep
+    tol = ATTN_GUARD[st.dtype] if tol is None else tol
+    assert tol <= ATTN_TOL and rep["nan"] == 0 and rep["max_abs_vs_f64"] <= tol, rep
     _say(f"attn {st.name} path={path} out={st.dtype}")
     out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens, **kw)
     torch.cuda.synchronize()
@@ -62,7 +70,7 @@ def check_attention(st, oracle, pkg, path="auto", tol=ATTN_TOL):
     return rep
 
 
-def check_accept(st, oracle, pkg, path="auto", out_stride=None, max_near_tie_frac=0.05):
+def check_accept(st, oracle, pkg, path="auto", out_stride=None, max_near_tie_frac=NEAR_TIE_FRAC):
     import torch
     dev = to_device(st, attention=False)
     _say(f"accept {st.name} path={path} B={st.batch} TQ={st.total_q} V={st.vocab}")
@@ -268,7 +276,7 @@ def test_attention_max_spec_len_larger_than_used(oracle_mod, pkg):
     out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens,
                           max_spec_len=8, out_dtype=F32)
     torch.cuda.synchronize()
-    assert compare_attention(out, ref, None, "bf16")["max_abs_vs_f64"] <= ATTN_TOL
+    assert compare_attention(out, ref, None, "bf16")["max_abs_vs_f64"] <= ATTN_GUARD["bf16"]
 
 
 def test_attention_custom_scale(oracle_mod, pkg):
@@ -316,7 +324,7 @@ def test_attention_sharp_scores_with_growing_maximum(dt, path, oracle_mod, pkg):
     torch.cuda.synchronize()
     rep = compare_attention(out, ref, None, dt)
     _say(f"attn sharp {rep}")
-    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_GUARD[dt], rep
 
 
 ACCEPT_EDGES = [

@@ -54,9 +54,9 @@ def _one_case(kind, case, seed, rng, oracle_mod, pkg, torch):
         d = int(rng.choice([64, 128])) if dt != "f32" else int(rng.choice([32, 64, 128]))
         st = W.make_custom_step(seed, ctx_lens=ctx, spec_lens=spec, n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d,
                                 dtype=dt, acceptance=False, name=f"random-attn-{seed}")
-        TP.check_attention(st, oracle_mod, pkg, tol=1e-5 if dt == "f32" else TP.ATTN_TOL)
+        TP.check_attention(st, oracle_mod, pkg)
         if case % 8 == 0:
-            TP.check_attention(st, oracle_mod, pkg, path="vector", tol=1e-5 if dt == "f32" else TP.ATTN_TOL)
+            TP.check_attention(st, oracle_mod, pkg, path="vector")
     elif kind == 1:    # tree attention
         B = int(rng.integers(1, 16))
         spec = rng.integers(0, 20, B).astype(np.int32)

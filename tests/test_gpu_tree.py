@@ -14,7 +14,9 @@ from oracle import kv_cache as KV
 from tests.harness import _torch_from, compare_accept_tree, compare_attention, to_device
 
 pytestmark = pytest.mark.gpu
-ATTN_TOL = 2e-3
+ATTN_TOL = 2e-3                                             # the benchmark's bar
+ATTN_GUARD = {"f32": 2e-5, "bf16": 2e-5, "f16": 1e-3}       # what the tests enforce (see test_gpu_parity.py)
+NEAR_TIE_FRAC = 0.025
 F32 = 0
 
 
@@ -43,7 +45,7 @@ def _check_tree_attention(st, oracle, pkg, path="auto"):
                           out_dtype=F32, **kw)
     torch.cuda.synchronize()
     rep = compare_attention(acc, ref, None, st.dtype)
-    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_GUARD[st.dtype], rep
     out = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens, **kw)
     out2 = pkg.verify_attn(dev.q, dev.k_pages, dev.v_pages, dev.block_table, dev.ctx_lens, dev.spec_lens, **kw)
     torch.cuda.synchronize()
@@ -53,7 +55,7 @@ def _check_tree_attention(st, oracle, pkg, path="auto"):
     return rep
 
 
-def _check_tree_accept(st, oracle, pkg, out_stride=None, max_near_tie_frac=0.05, kpath="auto"):
+def _check_tree_accept(st, oracle, pkg, out_stride=None, max_near_tie_frac=NEAR_TIE_FRAC, kpath="auto"):
     import torch
     dev = to_device(st, attention=False)
     _say(f"tree accept {st.name} path={kpath} B={st.batch} TQ={st.total_q} V={st.vocab}")
@@ -262,7 +264,7 @@ def test_tree_step_end_to_end(oracle_mod, pkg):
     ref, _ = oracle_mod.verify_attn_tree(st.q, k1, v1, st.block_table, st.ctx_lens, st.spec_lens, st.parents,
                                          dtype=st.dtype, want_rounded=False)
     rep = compare_attention(out, ref, None, st.dtype)
-    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_GUARD[st.dtype], rep
     arep = compare_accept_tree(st, toks.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), oracle_mod)
     assert arep["hard_mismatches"] == 0, arep["details"][:5]
     # compaction and commit are integer / byte work: exact, given the GPU's own path
@@ -410,7 +412,7 @@ def test_malformed_parents_are_forced_into_the_request(oracle_mod, pkg):
     ref, _ = oracle_mod.verify_attn_tree(st.q, st.k_pages, st.v_pages, st.block_table, st.ctx_lens, st.spec_lens,
                                          good, dtype=st.dtype, want_rounded=False)
     rep = compare_attention(out, ref, None, st.dtype)
-    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_TOL, rep
+    assert rep["nan"] == 0 and rep["max_abs_vs_f64"] <= ATTN_GUARD[st.dtype], rep
     for p, (toks, alen, path) in res.items():
         arep = compare_accept_tree(st, toks.cpu().numpy(), alen.cpu().numpy(), path.cpu().numpy(), oracle_mod)
         assert arep["hard_mismatches"] == 0, (p, arep["details"][:3])

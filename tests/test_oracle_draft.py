@@ -91,3 +91,32 @@ def test_greedy_takes_the_lowest_index_among_ties(oracle_mod):
     # greedy rows still carry the temperature-1 distribution
     ref = softmax(W.bf16_bits_to_f32(l).astype(np.float64), axis=1)
     assert np.all(np.abs(q - ref) <= 2.0 ** -8 * ref + 1e-40)
+
+
+def test_greedy_drafts_pair_with_greedy_verification_only(oracle_mod):
+    """Which pairing of draft and verification temperatures keeps the output the target's (Sec. 2.2):
+    a draft SAMPLED from its stored row q and verified at T > 0 does (chi-square over 200 000 trials); a
+    GREEDY draft (T == 0: token = arg-max, stored row = softmax at temperature 1) is not a draw from the row
+    it stores, so verifying it at T > 0 skews the output, while verifying it at T == 0, where q is not
+    looked at, reproduces greedy decoding exactly.  The library guarantees the first and the third."""
+    from tests.test_oracle_accept import _chi2_stat, _crit, _softmax64
+    V, n = 6, 200_000
+    rng = np.random.default_rng(21)
+    tl = rng.normal(0, 1.0, (2, V)).astype(np.float32)                 # target rows: draft position, bonus
+    dl = (tl[0] + rng.normal(0, 0.7, V)).astype(np.float32)            # the drafter's logits
+    p = _softmax64(tl[0])
+    spec, uni = np.ones(n, np.int32), rng.random((2 * n, 2), dtype=np.float32)
+    logits = np.tile(tl, (n, 1))
+
+    def first_tokens(draft_T, verify_T):
+        q, tok, _, _ = oracle_mod.draft_sample(np.tile(dl, (n, 1)), np.full(n, draft_T, np.float32),
+                                               rng.random(n, dtype=np.float32), logits_dtype="f32", probs_dtype="f32")
+        out, _, _ = oracle_mod.accept(logits, q.astype(np.float32), tok, uni, spec, np.full(n, verify_T, np.float32),
+                                      logits_dtype="f32", probs_dtype="f32", want_row_info=False)
+        return out[:, 0]
+
+    stat, dof = _chi2_stat(np.bincount(first_tokens(1.0, 1.0), minlength=V), p)
+    assert stat < _crit(dof), (stat, dof)                              # sampled draft, sampled verification: ~ p
+    stat, dof = _chi2_stat(np.bincount(first_tokens(0.0, 1.0), minlength=V), p)
+    assert stat > 10 * _crit(dof), (stat, dof)                         # greedy draft, sampled verification: NOT ~ p
+    assert np.all(first_tokens(0.0, 0.0) == int(np.argmax(tl[0])))     # greedy draft, greedy verification: arg-max
