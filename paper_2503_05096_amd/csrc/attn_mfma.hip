@@ -40,6 +40,7 @@ constexpr int kBlk = 32;                // tokens per block (two pages)
 constexpr int kWaves = 4;
 constexpr int kORowStride = 132;        // floats per row of the merge buffer (padded: conflict-free b128)
 constexpr float kNegBig = -1.0e30f;     // "no token seen yet": finite, so differences never give NaN
+constexpr float kLazyLog2 = 8.0f;       // a row's softmax reference trails its running maximum by at most this (log2 units)
 
 template <class T> struct Mma;
 template <> struct Mma<BF16> {
@@ -311,16 +312,28 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
                 mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
                 mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-                const float m_new = fmaxf(m[nt], mx * scale_log2);
-                const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
-                m[nt] = m_new;
+                // Lazy reference: the running reference m of a row moves only when the block's maximum exceeds it
+                // by more than kLazyLog2 (weights then stay below 2^kLazyLog2, harmless in fp32 and in the
+                // 16-bit operand formats), so the accumulators are rescaled in a handful of blocks per unit
+                // instead of in almost every one, and the rescaling sits on a cold path.
+                const float mxs = mx * scale_log2;
+                const bool grow = mxs > m[nt] + kLazyLog2;
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+                    const float m_new = grow ? mxs : m[nt];
+                    const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
+                    m[nt] = m_new;
+                    lsum[nt] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) o[nt][dt] *= alpha;
+                }
+                const float m_ref = m[nt];
                 float p[8], psum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], scale_log2, -m_new));
+                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], scale_log2, -m_ref));
                     psum += p[e];
                 }
-                lsum[nt] = lsum[nt] * alpha + psum;
+                lsum[nt] += psum;
                 pop[nt] = make_uint4(Mma<T>::pack2(p[0], p[1]), Mma<T>::pack2(p[2], p[3]),
                                      Mma<T>::pack2(p[4], p[5]), Mma<T>::pack2(p[6], p[7]));
                 if constexpr (Mma<T>::kSplitP) {
@@ -331,10 +344,6 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                         lo[w] = Mma<T>::pack2(p[2 * w] - __uint_as_float(hi[w] << 16),
                                               p[2 * w + 1] - __uint_as_float(hi[w] & 0xffff0000u));
                     pop_lo[nt] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-                }
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) o[nt][dt] *= alpha;
                 }
             }
 
