@@ -41,11 +41,12 @@ __host__ __device__ inline int split_len_of(int L, int ns, int block_tokens)
     return (per + block_tokens - 1) / block_tokens * block_tokens;
 }
 
-// Matrix-core kernel: 16-row query tiles one unit holds (1..3), and units per (item, kv head).
+// Matrix-core kernels: 16-row query tiles one unit holds and units per (item, kv head).  Up to 32 rows per
+// kv head: 1 or 2 tiles, the wavefronts of a workgroup split the unit's tokens (attn_mfma.hip); more: groups
+// of 4 tiles (64 rows), the wavefronts split the rows (attn_rows.hip).
 inline int attn_row_tiles(int max_rows)
 {
-    const int t = (max_rows + 15) / 16;
-    return t > 3 ? 3 : (t < 1 ? 1 : t);
+    return max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
 }
 inline int attn_row_groups(int max_rows)
 {
@@ -85,6 +86,9 @@ hipError_t launch_attn_plan(const AttnArgs &a);
 hipError_t launch_tree_masks(const AttnArgs &a);
 hipError_t launch_attn_vector(const AttnArgs &a);
 hipError_t launch_attn_mfma(const AttnArgs &a);
+// row-split form for units of more than 32 rows (attn_rows.hip); launch_attn_mfma forwards to it
+hipError_t launch_attn_rows(const AttnArgs &a);
+int attn_rows_grid_slots(const AttnArgs &a, int cus);   // resident workgroups = columns of the schedule table
 hipError_t launch_attn_combine(const AttnArgs &a);
 
 // ---- accept workspace ------------------------------------------------------

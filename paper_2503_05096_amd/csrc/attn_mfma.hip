@@ -24,79 +24,10 @@
 // row (bit a = node a is the row's node or an ancestor of it), prepared once per verification pass.
 // Only the blocks that hold new positions look at it; the instantiations for chains are untouched.
 #include "adaspec_internal.h"
+#include "attn_mfma_common.h"
 #include "device_utils.h"
 
 namespace adaspec {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kD = 128;                 // head_dim
-constexpr int kBlk = 32;                // tokens per block (two pages)
-constexpr int kWaves = 4;
-constexpr int kORowStride = 132;        // floats per row of the merge buffer (padded: conflict-free b128)
-constexpr float kNegBig = -1.0e30f;     // "no token seen yet": finite, so differences never give NaN
-constexpr float kLazyLog2 = 8.0f;       // a row's softmax reference trails its running maximum by at most this (log2 units)
-
-template <class T> struct Mma;
-template <> struct Mma<BF16> {
-    // bf16 keeps 8 significant bits: a softmax weight rounded to it is off by up to 2^-9 relative,
-    // which with a handful of dominant tokens reaches the 2e-3 output tolerance.  The weights are
-    // therefore fed to the matrix core as hi + lo (two bf16 values, 16 significant bits).
-    static constexpr bool kSplitP = true;
-    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
-    {
-        f32x2 x = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));   // v_cvt_pk_bf16_f32, RNE
-    }
-};
-template <> struct Mma<F16> {
-    static constexpr bool kSplitP = false;       // fp16 keeps 11 bits: 2^-12 relative is enough
-    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
-                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
-    {
-        f32x2 x = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));    // v_cvt_pk_f16_f32, RNE
-    }
-};
-
-__device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// K and V are read exactly once per work unit: stream them past the caches.
-__device__ __forceinline__ uint4 ld16_stream(const char *p)
-{
-    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
-}
-
-// V^T tile in LDS, in units of 16 bytes (= the 8 k-slots of one channel for one lane group):
-//   unit(d = 8c + dd, grp) = 66 dd + 16 grp + c
-// The writer lane (grp = tq, c) stores channel 8c + dd at its base + 66*16*dd bytes; the reader
-// lane (grp, m = 8h + dd') loads channel 16 dt + m = 8 (2dt + h) + dd' from its base + 32 dt bytes.
-// Within a 16-lane group both patterns hit 16 distinct 16-byte bank groups: conflict free.
-constexpr int kVtUnits = 66 * 7 + 64;
-constexpr int kVtBytes = ((kVtUnits * 16 + 255) / 256) * 256;
-
-// Everything a workgroup needs to know about one work unit; all wave-uniform.
-struct Unit {
-    int item, gkv, i, ns, L, n, rows, r0, t0, t1, nblk;
-    int64_t qrow0, bt_off;      // first query row; offset of the request's row in block_table
-};
 
 template <class T, int RT, bool kTree>
 __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
@@ -310,8 +241,7 @@ __global__ __launch_bounds__(256, (RT <= 2 ? 2 : 1)) void attn_mfma_kernel(
                 }
                 float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                                  fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-                mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+                mx = max_over_row_groups(mx);
                 // Lazy reference: the running reference m of a row moves only when the block's maximum exceeds it
                 // by more than kLazyLog2 (weights then stay below 2^kLazyLog2, harmless in fp32 and in the
                 // 16-bit operand formats), so the accumulators are rescaled in a handful of blocks per unit
@@ -515,11 +445,8 @@ template <typename F>
 static void with_instance(int dtype, int rt, bool tree, F &&f)
 {
     auto with_rt = [&](auto tag, auto tree_tag) {
-        switch (rt) {
-        case 1: f(tag, std::integral_constant<int, 1>{}, tree_tag); break;
-        case 2: f(tag, std::integral_constant<int, 2>{}, tree_tag); break;
-        default: f(tag, std::integral_constant<int, 3>{}, tree_tag); break;
-        }
+        if (rt == 1) f(tag, std::integral_constant<int, 1>{}, tree_tag);
+        else f(tag, std::integral_constant<int, 2>{}, tree_tag);
     };
     auto with_tree = [&](auto tag) {
         if (tree) with_rt(tag, std::true_type{});
@@ -537,9 +464,14 @@ void attn_mfma_shape(AttnArgs &a)
     a.rows_per_group = 16 * rt;
     const int64_t max_units = (int64_t)p.max_items * a.dims.n_kv_heads * a.n_row_groups;
     int slots = 1;
-    with_instance(a.dims.dtype, rt, a.parents != nullptr, [&](auto tag, auto rt_tag, auto tree_tag) {
-        slots = attn_mfma_slots<decltype(tag), decltype(rt_tag)::value, decltype(tree_tag)::value>();
-    });
+    if (rt > 2) {
+        slots = attn_rows_grid_slots(a, device_cus());               // more than 32 rows: the row-split kernel
+        if (slots <= 0) slots = device_cus();
+    } else {
+        with_instance(a.dims.dtype, rt, a.parents != nullptr, [&](auto tag, auto rt_tag, auto tree_tag) {
+            slots = attn_mfma_slots<decltype(tag), decltype(rt_tag)::value, decltype(tree_tag)::value>();
+        });
+    }
     a.sched_w = (int)(max_units < slots ? max_units : slots);
     a.sched_cus = device_cus();
 }
@@ -549,6 +481,7 @@ hipError_t launch_attn_mfma(const AttnArgs &a)
     const AttnPlan &p = a.plan;
     const adaspec_attn_dims &d = a.dims;
     if (a.sched_w <= 0) return hipSuccess;                          // no work item can exist
+    if (attn_row_tiles(p.max_rows) > 2) return launch_attn_rows(a);
     with_instance(d.dtype, attn_row_tiles(p.max_rows), a.parents != nullptr, [&](auto tag, auto rt_tag, auto tree_tag) {
         using T = decltype(tag);
         constexpr int RT = decltype(rt_tag)::value;
