@@ -204,9 +204,9 @@ size_t adaspec_accept_workspace_bytes(const adaspec_accept_dims *dims);
  * The register-resident and two-pass paths need 16-bit logits/probs of one type, V % 8 == 0,
  * V <= 131072, strides % 8 == 0 and 16-byte aligned base pointers; the streaming path takes the
  * same up to V <= 524288 (it reads the logits row twice, the second time from the caches);
- * anything else runs on the vector path.  AUTO: two-pass when it fits and either there are more
- * logits rows than compute units or V >= 65536, register-resident when it fits, streaming for
- * larger vocabularies, else vector.
+ * anything else runs on the vector path.  AUTO: two-pass when it fits (batches above 1024 requests:
+ * only with more logits rows than compute units or V >= 65536), register-resident when it fits,
+ * streaming for larger vocabularies, else vector.
  */
 int adaspec_accept(const void *target_logits, const void *draft_probs,
                    const int32_t *draft_tokens, const float *uniforms,

@@ -267,13 +267,15 @@ static int resolve_accept_path(const adaspec_accept_dims &d, const void *logits,
     if (d.path == ADASPEC_PATH_STREAM && !stream_ok) return ADASPEC_ERR_UNSUPPORTED;
     if (d.path == ADASPEC_PATH_TWO_PASS && !two_pass_ok) return ADASPEC_ERR_UNSUPPORTED;
     if (d.path != ADASPEC_PATH_AUTO) return d.path;
-    // AUTO.  The single-pass register-resident kernel is one row's latency: about 20 us at V = 32000, 36 us at
-    // V = 128256 (plus the emit kernel).  The two-pass form does less work per request and spreads the deciding
-    // row over four workgroups, but chains three kernels.  Measured on MI355X: V = 128256, 510 rows 48 against
-    // 60 + 4.6 us (streaming kernel + emit); 227 rows 32 against 36 + 4.3 us (all greedy: 23 against 16 + 4.3 us);
-    // V = 32000, 172 rows 23 against 20 + 4.6 us.  So: two-pass with more rows than compute units (the total
-    // work counts there) and for large vocabularies; a row that does not fit the registers of one workgroup
-    // (V > 131072) goes to the streaming kernel, anything else to the vector kernel.
+    // AUTO.  The two-pass form in row parts does the least work (rows behind a rejection are never read, the
+    // sampling step runs on one row per request) and spreads every row over many small workgroups; measured
+    // on MI355X it is ahead of the per-row kernels (+ emit kernel) on every benchmark shape: V = 32000, 150
+    // rows 16.5 against 21.4 us; V = 128256: 227 rows 28 against 38 us, 380 rows 39 against 63 us, 510 rows
+    // 42 against 70 us; all greedy 17.1 against 16.9 us.  Batches it does not take (more than 1024 requests)
+    // use the older two-pass pair when there are more rows than compute units or the vocabulary is large; a
+    // row that does not fit the registers of one workgroup (V > 131072) goes to the streaming kernel, anything
+    // else to the vector kernel.
+    if (two_pass_ok && accept_parts_supported(d)) return ADASPEC_PATH_TWO_PASS;
     if (two_pass_ok && (d.total_q > compute_units() || d.vocab >= 65536)) return ADASPEC_PATH_TWO_PASS;
     if (fast_ok) return ADASPEC_PATH_FAST;
     if (stream_ok) return ADASPEC_PATH_STREAM;

@@ -137,8 +137,9 @@ def test_config_accept_two_pass_path(cfg, greedy, oracle_mod, pkg):
 
 
 def test_auto_path_of_the_acceptance(pkg):
-    """AUTO: two-pass with more logits rows than compute units or a large vocabulary, register-resident
-    otherwise, streaming for vocabularies the registers cannot hold, vector for what none of them takes."""
+    """AUTO: the two-pass form whenever its shapes fit (16-bit rows of one type, V % 8 == 0, V <= 131072),
+    streaming for vocabularies the registers cannot hold, vector for what none of them takes; batches above
+    1024 requests take the two-pass form only with more rows than compute units or a large vocabulary."""
     import torch
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     def resolved(rows, V, dtype=torch.bfloat16, B=4):
@@ -148,10 +149,13 @@ def test_auto_path_of_the_acceptance(pkg):
         spec = torch.full((B,), (rows - B) // B, dtype=torch.int32, device="cuda:0")
         return pkg.accept_resolved_path(logits, probs, toks, spec, max_spec_len=(rows - B) // B)
     assert resolved(4 * (cus // 4 + 1), 4096) == "two_pass"
-    assert resolved(4 * (cus // 4), 4096) == "fast"
-    assert resolved(8, 65536) == "two_pass" and resolved(8, 65528) == "fast"
+    assert resolved(8, 4096) == "two_pass" and resolved(8, 131072) == "two_pass"
     assert resolved(8, 151936) == "stream"
     assert resolved(8, 4096, dtype=torch.float32) == "vector"
+    assert resolved(8, 4100) == "vector"                              # V % 8 != 0
+    assert resolved(2048, 4096, B=1024) == "two_pass"                 # the largest batch of the form in parts
+    assert resolved(2400, 8, B=1200) == "two_pass"                    # beyond it: more rows than compute units
+    assert resolved(2400, 8, B=1200) == resolved(2400, 8, B=1200)
 
 
 TWO_PASS_EDGES = [
