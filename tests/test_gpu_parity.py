@@ -255,7 +255,10 @@ EDGE_SHAPES = [
     ([257, 511, 513], [1, 0, 8], 16, 2, 64, "bf16"),  # GQA 8, 72 query rows, d = 64
     ([100, 200], [2, 1], 6, 3, 80, "f16"),            # head_dim the matrix-core path does not take
     ([2100], [5], 64, 8, 128, "bf16"),                # one long request: many splits, 48 rows
-    ([700, 90], [10, 7], 64, 8, 128, "f16"),          # 88 query rows per kv head: two row groups of 48
+    ([700, 90], [10, 7], 64, 8, 128, "f16"),          # 88 query rows per kv head: two row groups of 64 (row-split kernel)
+    ([5000, 33, 70], [7, 7, 0], 64, 8, 128, "bf16"),  # exactly 64 rows, several splits, beside tiny contexts and an 8-row request
+    ([3, 2], [2, 1], 64, 4, 128, "f16"),              # GQA 16: 48 rows whose context is only the new tokens
+    ([9000, 40], [3, 0], 128, 8, 128, "bf16"),        # GQA 16: 64 rows over five splits, and a 16-row request
     ([4097, 4096, 4095], [0, 1, 2], 8, 1, 128, "bf16"),   # just around a split boundary, one kv head
     ([65536, 40001], [2, 5], 8, 2, 128, "bf16"),      # very long contexts: up to 256 splits per request to combine
 ]
