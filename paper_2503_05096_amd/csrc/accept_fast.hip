@@ -19,10 +19,12 @@
 //   4. inside step it*: fp64 scan over wavefronts and lanes -> the owning thread,
 //      which walks its 8 elements
 // Per-element arithmetic is fp32; every sum across threads is fp64.
-// The best kernel while every row has a compute unit to itself.  With more rows than
-// compute units the two-pass form takes over: the streaming kernel (accept_stream.hip) in
-// test-only mode judges every draft row, then this kernel in resolve mode runs steps 1-4
-// once per REQUEST, on the row that decides its token, and writes the request's outputs.
+// A per-row form: every logits row is evaluated completely, the emit kernel applies the sequential rule
+// afterwards.  AUTO prefers the two-pass form in row parts (accept_parts.hip), which reads less and spreads
+// every row over many workgroups; this kernel remains as a forced path, and in resolve mode as the second
+// pass of batches above 1024 requests: the streaming kernel (accept_stream.hip) in test-only mode judges
+// every draft row, then this kernel runs steps 1-4 once per REQUEST, on the row that decides its token, and
+// writes the request's outputs.
 #include "adaspec_internal.h"
 #include "device_utils.h"
 #include "row_registers.h"

@@ -1,9 +1,8 @@
 // Streaming acceptance kernel for gfx950: 16-bit logits and draft probabilities, V % 8 == 0,
 // V <= 524288.  Same rule and same per-row results (flag, candidate) as the other two acceptance
-// kernels.  It serves vocabularies too large for the register-resident kernel, and any batch with
-// more logits rows than compute units: it needs at most 64 registers per thread and 73 KB of LDS, so
-// TWO workgroups (rows) share a compute unit and one row's compute and latency phases overlap the
-// other's memory phases.
+// kernels.  It serves vocabularies too large for the register-resident kernel and the two-pass form
+// (V > 131072): it needs at most 64 registers per thread and 73 KB of LDS, so TWO workgroups (rows)
+// share a compute unit and one row's compute and latency phases overlap the other's memory phases.
 //
 // One workgroup of 1024 threads per logits row, 16 bytes = 8 elements per thread per step of 8192:
 //   stash    steps 0..3 of the row go from memory straight into LDS (no registers), requested before
@@ -58,7 +57,8 @@ __device__ __forceinline__ uint4 kept_step(int s, const uint4 &k0, const uint4 &
     return v;
 }
 
-// kTestOnly: the first pass of the two-pass form (see accept_fast.hip, resolve mode).  Only draft rows
+// kTestOnly: the first pass of the two-pass form for batches above 1024 requests (second pass: accept_fast.hip,
+// resolve mode; smaller batches take accept_parts.hip).  Only draft rows
 // are judged: sweep 1, the accept test, the flag (greedy rows also leave their arg-max as candidate),
 // and the workgroup is done; bonus rows leave at once.  Nothing of sweep 2 is compiled in.
 template <class DT, bool kTestOnly>
