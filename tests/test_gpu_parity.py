@@ -462,6 +462,34 @@ def test_more_than_1024_requests(oracle_mod, pkg):
     check_accept(st, oracle_mod, pkg, path="two_pass")
 
 
+def test_accept_two_pass_at_the_limits_of_the_form_in_parts(oracle_mod, pkg):
+    """1000 requests (the in-kernel scan of the form in parts takes four requests per thread, up to 1024), and a
+    batch whose slot count batch * max_spec_len exceeds what that form lays out, which takes the older pair of
+    kernels: both against the oracle."""
+    rng = np.random.default_rng(1000)
+    B = 1000
+    spec = rng.integers(0, 4, B).astype(np.int32)
+    st = W.make_custom_step(1000, ctx_lens=spec + 9, spec_lens=spec, vocab=2048, logits_dtype="bf16",
+                            temperature=rng.choice(np.array([0.0, 0.8, 1.0], np.float32), B), attention=False,
+                            logits_sigma=3.0, noise_sigma=1.0, draft_temp=1.1, name="b1000")
+    check_accept(st, oracle_mod, pkg, path="two_pass")
+    check_accept(st, oracle_mod, pkg)                               # AUTO takes the same form
+    B = 600
+    spec = rng.integers(0, 5, B).astype(np.int32)
+    st = W.make_custom_step(1001, ctx_lens=spec + 9, spec_lens=spec, vocab=1024, logits_dtype="f16",
+                            temperature=rng.choice(np.array([0.0, 0.9], np.float32), B), attention=False,
+                            logits_sigma=3.0, noise_sigma=1.0, draft_temp=1.1, name="b600-wide-slots")
+    import torch
+    dev = to_device(st, attention=False)
+    _say(f"accept {st.name} max_spec_len=64 (600 x 64 slots: beyond the form in parts)")
+    toks, alen = pkg.accept(dev.target_logits, dev.draft_probs, dev.draft_tokens, dev.uniforms, dev.spec_lens,
+                            dev.temperature, max_spec_len=64, path="two_pass")
+    torch.cuda.synchronize()
+    rep = compare_accept(st, toks.cpu().numpy()[:, :st.max_spec_len + 1], alen.cpu().numpy(), oracle_mod)
+    assert rep["hard_mismatches"] == 0, rep["details"][:5]
+    assert torch.all(toks[:, st.max_spec_len + 1:] == -1)
+
+
 def test_more_work_items_than_the_plan_keeps_on_chip(oracle_mod, pkg):
     """One request with a very long context makes the block table wide, so the host-side bound on the work
     items (requests x splits of the widest context) exceeds what the plan kernel holds in LDS: it then reads
