@@ -195,3 +195,18 @@ def test_masked_logits_option():
     assert not np.isnan(q).any() and (q[masked[keep]] == 0).all()      # the draft puts no mass on masked tokens
     for d in range(st.total_draft):
         assert q[d, st.draft_tokens[d]] > 0
+
+
+def test_policy_inputs_and_policy_shaped_step():
+    """The synthetic inputs of the speculative-length policy are seeded and hold draws only; the step built
+    from a vector of draft lengths has ctx_lens = committed + k + 1 and the config's tensor shapes."""
+    a, b = W.policy_inputs(3, batch=12), W.policy_inputs(3, batch=12)
+    assert np.array_equal(a["ctx_committed"], b["ctx_committed"]) and np.array_equal(a["conf"], b["conf"])
+    assert a["conf"].shape == (8, 12) and a["conf"].dtype == np.float64
+    assert np.all(a["conf"] > 0) and np.all(a["conf"] <= 1) and 0 < a["prev_conf"] < 1
+    assert not np.array_equal(a["conf"], W.policy_inputs(3, batch=12, seed=7)["conf"])
+    k = np.arange(12, dtype=np.int32) % 5
+    st = W.make_policy_step(a, k, attention=False)
+    assert np.array_equal(st.spec_lens, k) and np.array_equal(st.ctx_lens, a["ctx_committed"] + k + 1)
+    assert st.vocab == W.CONFIGS[3]["vocab"] and st.total_q == int((k + 1).sum()) and st.name.endswith("-policy")
+    assert np.array_equal(st.temperature, a["temperature"])
