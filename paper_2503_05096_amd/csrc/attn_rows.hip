@@ -55,7 +55,7 @@ __device__ __forceinline__ v4i32 page_rsrc(const char *p)
 // 16 bytes per lane from memory straight into LDS: lane i lands at lds_addr + 16 i (M0 carries the LDS address;
 // the data never passes through registers).  Written in assembly on purpose: the compiler, not knowing which
 // LDS bytes such a load will write, would make every later LDS read wait until ALL loads in flight have landed,
-// and the point of the ring is that three blocks stay in flight.  The kernel waits for the block it needs itself
+// and the point of the ring is that several blocks stay in flight.  The kernel waits for the block it needs itself
 // (s_waitcnt vmcnt with the number of younger loads) before the barrier that publishes it.
 // Two such loads behind one M0: the second lands 1024 bytes further in LDS; the instruction's offset field
 // moves the memory address by the same 1024 bytes, which lane_offset1 has been reduced by.
